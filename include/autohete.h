@@ -1,0 +1,166 @@
+/*
+ * autohete.h -- C ABI of the MI355X (gfx950) chunked mixed-precision AdamW update.
+ *
+ * The operation is the GPU optimizer update of AutoHete (cost t_optim^gpu, charged on
+ * the backward compute stream in Eq. 5, first arm) over "model data" as section 2.1
+ * defines it: 16-bit parameters and gradients plus fp32 optimizer states (momentum,
+ * variance, fp32 parameter copy), 16 bytes per parameter.  Model data is packed into
+ * fixed-size flat chunks (section 3.1: transfers aggregate tensors; section 3.4:
+ * parameters are mapped to device memory in advance).  The paper names Adam and gives
+ * no equations; the rule implemented is Adam with decoupled weight decay, preceded by
+ * loss-scale removal, a finite check and global-L2-norm clipping:
+ *
+ *     S     = extra_sumsq + sum over all chunk elements of (grad / loss_scale)^2
+ *     skip  = any non-finite gradient, or S non-finite     -> nothing is modified
+ *     c     = max_grad_norm > 0 ? min(1, max_grad_norm / (sqrt(S) + 1e-6)) : 1
+ *     g     = grad / loss_scale * c
+ *     m'    = beta1 m + (1 - beta1) g
+ *     v'    = beta2 v + (1 - beta2) g^2
+ *     p'    = p - lr ( (m' / (1 - beta1^t)) / (sqrt(v' / (1 - beta2^t)) + eps) + weight_decay p )
+ *     p16'  = round-to-nearest-even(p') in bf16 or fp16
+ *
+ * Conventions
+ *   - Every function returns an int status (AH_OK = 0, negative = error); nothing is
+ *     thrown or printed.  autohete_strerror() names a status.
+ *   - "device pointer" = address in the HBM of the current HIP device; "host pointer" =
+ *     ordinary process memory.  The caller owns every buffer it passes; the library owns
+ *     only the workspace object.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return, except where a host output is requested (stated below).
+ *   - One workspace serves one stream at a time: calls that use the same workspace must
+ *     be issued in stream order from one host thread.
+ */
+#ifndef AUTOHETE_H
+#define AUTOHETE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    AH_OK = 0,
+    AH_EINVAL = -1, /* null pointer, bad enum, numel == 0, step == 0, bad hyper-parameter */
+    AH_EALIGN = -2, /* a device pointer is not 16-byte aligned */
+    AH_ENOMEM = -3, /* allocation failed, or more chunks than the workspace was made for */
+    AH_EHIP = -4    /* a HIP runtime call failed */
+};
+
+enum { AH_BF16 = 0, AH_FP16 = 1 }; /* format of the two 16-bit streams */
+
+/*
+ * Chunk layout (host only, integer only; sections 3.1 and 3.4).
+ * Tensors are packed back to back, in the order given, into one flat element space that
+ * is cut into chunks of chunk_elems elements.  Tensor t occupies flat elements
+ * [tensor_offset[t], tensor_offset[t] + tensor_numel[t]); its first element lies in chunk
+ * tensor_offset[t] / chunk_elems at position tensor_offset[t] % chunk_elems; a tensor may
+ * straddle chunks.  Only the last chunk is padded.
+ *   tensor_numel   host in : n_tensors sizes (elements); may be NULL iff n_tensors == 0
+ *   tensor_offset  host out: n_tensors flat offsets (exclusive prefix sum); may be NULL
+ *   n_chunks       host out: ceil(total / chunk_elems)
+ *   total_elems    host out: sum of sizes
+ *   padded_elems   host out: n_chunks * chunk_elems - total
+ * Errors: AH_EINVAL if chunk_elems == 0, an out pointer (other than tensor_offset) is
+ * NULL, or the total overflows 64 bits.
+ */
+int autohete_chunk_layout(const uint64_t *tensor_numel, uint64_t n_tensors, uint64_t chunk_elems,
+                          uint64_t *tensor_offset, uint64_t *n_chunks, uint64_t *total_elems,
+                          uint64_t *padded_elems);
+
+/*
+ * One chunk of model data (section 2.1): five element-aligned streams of `numel`
+ * elements, all DEVICE pointers, each 16-byte aligned, none overlapping another.
+ */
+typedef struct {
+    const void *grad; /* 16-bit gradients, still multiplied by the loss scale; read only  */
+    void *param_lp;   /* 16-bit parameters; write only (derived from master)              */
+    float *master;    /* fp32 parameter copy; read and written in place                   */
+    float *exp_avg;   /* fp32 first moment m; read and written in place                   */
+    float *exp_avg_sq;/* fp32 second moment v >= 0; read and written in place             */
+    uint64_t numel;   /* elements to process, padding included; >= 1, any value           */
+} autohete_chunk;
+
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    float max_grad_norm; /* <= 0: no clipping */
+    float loss_scale;    /* > 0 and finite */
+} autohete_hparams;
+
+/*
+ * Workspace: device scratch for the cross-block norm reduction, the 16-byte reduction
+ * result, and device copies of the chunk tables.  max_chunks bounds n_chunks of later
+ * calls.  Create/destroy allocate/free device memory on the current device and
+ * synchronise it; do not call them inside a timed region.
+ */
+typedef struct autohete_ws autohete_ws;
+int autohete_ws_create(autohete_ws **ws, uint64_t max_chunks);
+int autohete_ws_destroy(autohete_ws *ws);
+
+/*
+ * Gradient preparation: loss-scale removal, finite check and global L2 norm over the
+ * given chunks in one streaming pass (2 bytes read per element).  The per-element
+ * gradients are not modified; the result {S, norm, skip flag} is left in the workspace
+ * on the device for autohete_adamw_step.
+ *   chunks        host in : n_chunks descriptors (device pointers inside); only .grad
+ *                           and .numel are used here
+ *   n_chunks      may be 0 (then S = extra_sumsq)
+ *   lowp_dtype    AH_BF16 or AH_FP16
+ *   loss_scale    > 0, finite
+ *   extra_sumsq   sum of squares of UNSCALED gradients that live elsewhere (chunks kept in
+ *                 host memory, other devices); 0 if none.  Non-finite raises the skip flag.
+ *   norm_out, found_inf_out   host out, each may be NULL.  If either is non-NULL the call
+ *                 waits for the stream and stores sqrt(S) (NaN when skipping) and the flag.
+ * The sum is accumulated in fp64 and is bit-reproducible for a given chunk list and
+ * workspace tuning.  Errors: AH_EINVAL, AH_EALIGN, AH_ENOMEM (n_chunks > max_chunks), AH_EHIP.
+ */
+int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
+                       int lowp_dtype, float loss_scale, double extra_sumsq, void *stream,
+                       float *norm_out, uint32_t *found_inf_out);
+
+/*
+ * The update (rule at the top of this file) over the given chunks in one fused pass:
+ * 14 bytes read and 14 bytes written per element; the states are touched once
+ * (appendix, "accessed only once for optimizer updates").  It consumes the workspace's
+ * device-side result, so it must follow an autohete_grad_prep (or
+ * autohete_grad_result_set) on the same stream.  If the skip flag is set the kernel
+ * exits before its first load and every stream is left bit-identical; the caller should
+ * then not advance `step`.  The chunk list may be any subset or partition of the list
+ * given to autohete_grad_prep (one optimizer per transformer block: footnote to Eq. 5),
+ * and per-element results do not depend on that grouping.
+ *   step   the 1-based t of the bias corrections; the library keeps no counter
+ *   hp     host in; loss_scale must be the value given to autohete_grad_prep
+ * Errors: AH_EINVAL (also: beta outside [0,1), lr/eps/weight_decay negative or
+ * non-finite), AH_EALIGN, AH_ENOMEM, AH_EHIP.
+ */
+int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
+                        int lowp_dtype, uint64_t step, const autohete_hparams *hp, void *stream);
+
+/*
+ * Read (waits for the stream) or overwrite (enqueued on the stream) the workspace's
+ * gradient result.  Setting it lets a caller step a block with a norm obtained elsewhere
+ * -- e.g. per-block stepping during backward with clipping off (sumsq = 0), or with the
+ * previous iteration's norm.  Any out pointer may be NULL.
+ */
+int autohete_grad_result_get(autohete_ws *ws, void *stream, double *sumsq, float *norm,
+                             uint32_t *found_inf);
+int autohete_grad_result_set(autohete_ws *ws, double sumsq, uint32_t found_inf, void *stream);
+
+/*
+ * Launch tuning (optional; defaults are chosen for MI355X).  Changing a knob never
+ * changes the update's results; AH_TUNE_PREP_BLOCKS changes the summation order of the
+ * norm (last bits of S).
+ */
+enum {
+    AH_TUNE_STEP_BLOCKS = 0, /* resident thread blocks of the step kernel; 0 = default      */
+    AH_TUNE_PREP_BLOCKS = 1, /* thread blocks of the prep kernel; 0 = default               */
+    AH_TUNE_STEP_VARIANT = 2 /* kernel variant index, see autohete_kernels.hip; 0 = default */
+};
+int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value);
+
+const char *autohete_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUTOHETE_H */

@@ -1,0 +1,330 @@
+/*
+ * autohete_api.hip -- host side of libautohete.so: the C ABI declared in include/autohete.h.
+ * Argument validation, the chunk layout, the workspace (device scratch + device copies of the
+ * chunk tables, re-uploaded only when a call's chunk list differs from the previous one), and
+ * the fp64 preparation of the per-launch constants.  All per-element work is in the kernels.
+ */
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/autohete.h"
+#include "autohete_internal.h"
+
+using ah::DevChunk;
+using ah::GradResult;
+
+struct autohete_ws {
+    int device = 0;
+    int n_cu = 0;
+    uint64_t max_chunks = 0;
+    /* slot 0: table of the last grad_prep call, slot 1: of the last adamw_step call */
+    DevChunk *d_tab[2] = {nullptr, nullptr};
+    DevChunk *h_stage[2] = {nullptr, nullptr}; /* pinned staging for the async upload */
+    std::vector<DevChunk> h_last[2];            /* what d_tab holds */
+    uint64_t last_tiles[2] = {0, 0};
+    hipEvent_t staged[2] = {nullptr, nullptr};  /* upload from h_stage has completed */
+    bool staged_pending[2] = {false, false};
+    double *d_partials = nullptr;
+    uint32_t *d_ticket = nullptr;
+    GradResult *d_res = nullptr;
+    GradResult *h_res = nullptr;                /* pinned read-back */
+    int64_t tune_step_blocks = 0, tune_prep_blocks = 0, tune_step_variant = 0;
+    int occ_cache[2][64];                       /* resident blocks/CU per dtype and variant */
+    int prep_occ[2] = {0, 0};
+};
+
+namespace {
+
+/* Default variant: 2x unroll, fp64 moments with fp32 root/quotient, non-temporal accesses.
+ * Encoding of AH_TUNE_STEP_VARIANT: unroll | mode << 4 | nt << 8. */
+constexpr int64_t kDefaultVariant = 2 | (0 << 4) | (1 << 8);
+
+bool decode_variant(int64_t v, ah::StepVariant *out)
+{
+    if (v == 0) v = kDefaultVariant;
+    ah::StepVariant s{(int)(v & 0xF), (int)((v >> 4) & 0xF), (int)((v >> 8) & 0xF)};
+    if (!(s.unroll == 1 || s.unroll == 2 || s.unroll == 4) || s.mode > 1 || s.nt > 1 || (v >> 12)) return false;
+    *out = s;
+    return true;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+/* Validate the caller's chunks and build the device table for tiles of tile_elems.
+ * need_all: the step needs all five streams, the prep only the gradients. */
+int build_table(autohete_ws *ws, int slot, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
+                bool need_all, hipStream_t stream, uint64_t *total_tiles)
+{
+    if (n > ws->max_chunks) return AH_ENOMEM;
+    if (n && !chunks) return AH_EINVAL;
+    std::vector<DevChunk> tab(n + 1);
+    uint64_t tiles = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        const autohete_chunk &c = chunks[i];
+        if (c.numel == 0 || !c.grad) return AH_EINVAL;
+        if (need_all && (!c.param_lp || !c.master || !c.exp_avg || !c.exp_avg_sq)) return AH_EINVAL;
+        if (!aligned16(c.grad)) return AH_EALIGN;
+        if (need_all && !(aligned16(c.param_lp) && aligned16(c.master) && aligned16(c.exp_avg) &&
+                          aligned16(c.exp_avg_sq)))
+            return AH_EALIGN;
+        DevChunk &d = tab[i];
+        d.grad = static_cast<const uint16_t *>(c.grad);
+        d.param_lp = static_cast<uint16_t *>(c.param_lp);
+        d.master = c.master;
+        d.exp_avg = c.exp_avg;
+        d.exp_avg_sq = c.exp_avg_sq;
+        d.numel = c.numel;
+        d.tile_begin = tiles;
+        d.reserved = 0;
+        tiles += (c.numel + tile_elems - 1) / tile_elems;
+    }
+    memset(&tab[n], 0, sizeof(DevChunk));
+    tab[n].tile_begin = tiles; /* sentinel */
+    *total_tiles = tiles;
+
+    std::vector<DevChunk> &last = ws->h_last[slot];
+    if (last.size() == tab.size() && memcmp(last.data(), tab.data(), tab.size() * sizeof(DevChunk)) == 0)
+        return AH_OK; /* device copy is current */
+
+    if (ws->staged_pending[slot]) { /* the previous upload may still be reading the staging buffer */
+        if (hipEventSynchronize(ws->staged[slot]) != hipSuccess) return AH_EHIP;
+        ws->staged_pending[slot] = false;
+    }
+    memcpy(ws->h_stage[slot], tab.data(), tab.size() * sizeof(DevChunk));
+    if (hipMemcpyAsync(ws->d_tab[slot], ws->h_stage[slot], tab.size() * sizeof(DevChunk), hipMemcpyHostToDevice,
+                       stream) != hipSuccess)
+        return AH_EHIP;
+    if (hipEventRecord(ws->staged[slot], stream) != hipSuccess) return AH_EHIP;
+    ws->staged_pending[slot] = true;
+    last.swap(tab);
+    return AH_OK;
+}
+
+struct DeviceGuard { /* run on the workspace's device, restore the caller's afterwards */
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard()
+    {
+        if (ok && prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char *autohete_strerror(int status)
+{
+    switch (status) {
+        case AH_OK: return "ok";
+        case AH_EINVAL: return "invalid argument";
+        case AH_EALIGN: return "device pointer not 16-byte aligned";
+        case AH_ENOMEM: return "out of memory or more chunks than the workspace holds";
+        case AH_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int autohete_chunk_layout(const uint64_t *tensor_numel, uint64_t n_tensors, uint64_t chunk_elems,
+                          uint64_t *tensor_offset, uint64_t *n_chunks, uint64_t *total_elems,
+                          uint64_t *padded_elems)
+{
+    if (chunk_elems == 0 || !n_chunks || !total_elems || !padded_elems) return AH_EINVAL;
+    if (n_tensors && !tensor_numel) return AH_EINVAL;
+    uint64_t run = 0;
+    for (uint64_t t = 0; t < n_tensors; ++t) {
+        if (tensor_offset) tensor_offset[t] = run;
+        if (__builtin_add_overflow(run, tensor_numel[t], &run)) return AH_EINVAL;
+    }
+    const uint64_t full = run / chunk_elems, rem = run % chunk_elems;
+    *n_chunks = full + (rem ? 1 : 0);
+    *total_elems = run;
+    *padded_elems = rem ? chunk_elems - rem : 0;
+    return AH_OK;
+}
+
+int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
+{
+    if (!out || max_chunks == 0 || max_chunks > (1u << 24)) return AH_EINVAL;
+    *out = nullptr;
+    autohete_ws *ws = new (std::nothrow) autohete_ws;
+    if (!ws) return AH_ENOMEM;
+    ws->max_chunks = max_chunks;
+    memset(ws->occ_cache, 0, sizeof(ws->occ_cache));
+    hipDeviceProp_t prop;
+    bool ok = hipGetDevice(&ws->device) == hipSuccess && hipGetDeviceProperties(&prop, ws->device) == hipSuccess;
+    if (ok) ws->n_cu = prop.multiProcessorCount;
+    const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
+    for (int s = 0; ok && s < 2; ++s) {
+        ok = hipMalloc(&ws->d_tab[s], tab_bytes) == hipSuccess &&
+             hipHostMalloc(&ws->h_stage[s], tab_bytes, hipHostMallocDefault) == hipSuccess &&
+             hipEventCreateWithFlags(&ws->staged[s], hipEventDisableTiming) == hipSuccess;
+    }
+    ok = ok && hipMalloc(&ws->d_partials, ah::kMaxPartials * sizeof(double)) == hipSuccess &&
+         hipMalloc(&ws->d_ticket, 256) == hipSuccess && hipMalloc(&ws->d_res, 256) == hipSuccess &&
+         hipHostMalloc(&ws->h_res, sizeof(GradResult), hipHostMallocDefault) == hipSuccess;
+    /* The ticket must start at zero (each prep launch re-arms it); the result starts as
+     * "no gradient seen": S = 0, no skip. */
+    ok = ok && hipMemset(ws->d_ticket, 0, 256) == hipSuccess && hipMemset(ws->d_res, 0, 256) == hipSuccess &&
+         hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        autohete_ws_destroy(ws);
+        return AH_ENOMEM;
+    }
+    *out = ws;
+    return AH_OK;
+}
+
+int autohete_ws_destroy(autohete_ws *ws)
+{
+    if (!ws) return AH_EINVAL;
+    DeviceGuard g(ws->device);
+    (void)hipDeviceSynchronize();
+    for (int s = 0; s < 2; ++s) {
+        if (ws->d_tab[s]) (void)hipFree(ws->d_tab[s]);
+        if (ws->h_stage[s]) (void)hipHostFree(ws->h_stage[s]);
+        if (ws->staged[s]) (void)hipEventDestroy(ws->staged[s]);
+    }
+    if (ws->d_partials) (void)hipFree(ws->d_partials);
+    if (ws->d_ticket) (void)hipFree(ws->d_ticket);
+    if (ws->d_res) (void)hipFree(ws->d_res);
+    if (ws->h_res) (void)hipHostFree(ws->h_res);
+    delete ws;
+    return AH_OK;
+}
+
+int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value)
+{
+    if (!ws || value < 0) return AH_EINVAL;
+    switch (knob) {
+        case AH_TUNE_STEP_BLOCKS:
+            if (value > (1 << 30)) return AH_EINVAL;
+            ws->tune_step_blocks = value;
+            return AH_OK;
+        case AH_TUNE_PREP_BLOCKS:
+            if (value > ah::kMaxPartials) return AH_EINVAL;
+            ws->tune_prep_blocks = value;
+            return AH_OK;
+        case AH_TUNE_STEP_VARIANT: {
+            ah::StepVariant v;
+            if (!decode_variant(value, &v)) return AH_EINVAL;
+            ws->tune_step_variant = value;
+            return AH_OK;
+        }
+        default: return AH_EINVAL;
+    }
+}
+
+static int read_result(autohete_ws *ws, hipStream_t stream, double *sumsq, float *norm, uint32_t *found_inf)
+{
+    if (hipMemcpyAsync(ws->h_res, ws->d_res, sizeof(GradResult), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return AH_EHIP;
+    if (sumsq) *sumsq = ws->h_res->sumsq;
+    if (norm) *norm = ws->h_res->norm;
+    if (found_inf) *found_inf = ws->h_res->found_inf;
+    return AH_OK;
+}
+
+int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                       float loss_scale, double extra_sumsq, void *stream_, float *norm_out,
+                       uint32_t *found_inf_out)
+{
+    if (!ws || (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16)) return AH_EINVAL;
+    if (!(loss_scale > 0.0f) || !isfinite(loss_scale)) return AH_EINVAL;
+    DeviceGuard g(ws->device);
+    if (!g.ok) return AH_EHIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    uint64_t tiles = 0;
+    int rc = build_table(ws, 0, chunks, n_chunks, ah::prep_tile_elems(), false, stream, &tiles);
+    if (rc != AH_OK) return rc;
+
+    int &occ = ws->prep_occ[lowp_dtype];
+    if (occ == 0) occ = ah::prep_occupancy(lowp_dtype);
+    if (occ <= 0) return AH_EHIP;
+    uint64_t blocks = ws->tune_prep_blocks ? (uint64_t)ws->tune_prep_blocks : (uint64_t)ws->n_cu * occ;
+    if (blocks > (uint64_t)ah::kMaxPartials) blocks = ah::kMaxPartials;
+    if (blocks > tiles) blocks = tiles;
+    if (ah::launch_prep(lowp_dtype, (unsigned)blocks, stream, ws->d_tab[0], (uint32_t)n_chunks, tiles,
+                        1.0 / (double)loss_scale, extra_sumsq, ws->d_partials, ws->d_ticket,
+                        ws->d_res) != hipSuccess)
+        return AH_EHIP;
+    if (norm_out || found_inf_out) return read_result(ws, stream, nullptr, norm_out, found_inf_out);
+    return AH_OK;
+}
+
+int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                        uint64_t step, const autohete_hparams *hp, void *stream_)
+{
+    if (!ws || !hp || step == 0 || (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16)) return AH_EINVAL;
+    auto nonneg = [](float x) { return isfinite(x) && x >= 0.0f; };
+    if (!nonneg(hp->lr) || !nonneg(hp->eps) || !nonneg(hp->weight_decay) || !isfinite(hp->max_grad_norm) ||
+        !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) ||
+        !(hp->loss_scale > 0.0f) || !isfinite(hp->loss_scale))
+        return AH_EINVAL;
+    DeviceGuard g(ws->device);
+    if (!g.ok) return AH_EHIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    ah::StepVariant var;
+    if (!decode_variant(ws->tune_step_variant, &var)) return AH_EINVAL;
+    uint64_t tiles = 0;
+    int rc = build_table(ws, 1, chunks, n_chunks, ah::step_tile_elems(var.unroll), true, stream, &tiles);
+    if (rc != AH_OK) return rc;
+    if (tiles == 0) return AH_OK;
+
+    /* Per-launch constants, fp64 from the fp32 hyper-parameters. */
+    ah::StepConsts k;
+    k.inv_scale = 1.0 / (double)hp->loss_scale;
+    k.max_norm = (double)hp->max_grad_norm;
+    k.b1 = (double)hp->beta1;
+    k.b2 = (double)hp->beta2;
+    k.omb1 = 1.0 - k.b1;
+    k.omb2 = 1.0 - k.b2;
+    k.bc1 = 1.0 - pow(k.b1, (double)step);
+    k.bc2 = 1.0 - pow(k.b2, (double)step);
+    k.rbc1 = 1.0 / k.bc1;
+    k.rbc2 = 1.0 / k.bc2;
+    k.lr = (double)hp->lr;
+    k.eps = (double)hp->eps;
+    k.wd = (double)hp->weight_decay;
+
+    const int vidx = (var.unroll == 1 ? 0 : var.unroll == 2 ? 1 : 2) + 3 * var.mode + 6 * var.nt;
+    int &occ = ws->occ_cache[lowp_dtype][vidx];
+    if (occ == 0) occ = ah::step_occupancy(lowp_dtype, var);
+    if (occ <= 0) return AH_EHIP;
+    uint64_t blocks = ws->tune_step_blocks ? (uint64_t)ws->tune_step_blocks : (uint64_t)ws->n_cu * occ;
+    if (blocks > tiles) blocks = tiles;
+    if (ah::launch_step(lowp_dtype, var, (unsigned)blocks, stream, ws->d_tab[1], (uint32_t)n_chunks, tiles,
+                        ws->d_res, k) != hipSuccess)
+        return AH_EHIP;
+    return AH_OK;
+}
+
+int autohete_grad_result_get(autohete_ws *ws, void *stream, double *sumsq, float *norm, uint32_t *found_inf)
+{
+    if (!ws) return AH_EINVAL;
+    DeviceGuard g(ws->device);
+    if (!g.ok) return AH_EHIP;
+    return read_result(ws, static_cast<hipStream_t>(stream), sumsq, norm, found_inf);
+}
+
+int autohete_grad_result_set(autohete_ws *ws, double sumsq, uint32_t found_inf, void *stream)
+{
+    if (!ws) return AH_EINVAL;
+    DeviceGuard g(ws->device);
+    if (!g.ok) return AH_EHIP;
+    return ah::launch_set_result(static_cast<hipStream_t>(stream), ws->d_res, sumsq, found_inf) == hipSuccess
+               ? AH_OK : AH_EHIP;
+}
+
+}  // extern "C"

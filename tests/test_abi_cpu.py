@@ -1,0 +1,78 @@
+"""CPU-only checks of the boundary: the library loads, exports what include/autohete.h
+declares, and its host-only logic (chunk layout, argument validation that needs no device)
+agrees with the oracle / the header."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_01890_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in os.listdir(inc):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(autohete_\w+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    syms = declared_symbols()
+    assert {"autohete_chunk_layout", "autohete_grad_prep", "autohete_adamw_step"} <= syms
+    lib = B.raw()
+    for s in sorted(syms):
+        assert hasattr(lib, s), s
+
+
+def test_chunk_layout_matches_oracle():
+    rng = np.random.default_rng(5)
+    for n, C in ((0, 8), (1, 1), (300, 4096), (2000, 2 ** 23), (50, 7)):
+        sizes = rng.integers(1, 3_000_000, n).astype(np.uint64)
+        got = B.autohete_chunk_layout(list(sizes), C)
+        off, nc, tot, pad = oracle.chunk_layout(sizes, C)
+        assert got == (list(off), nc, tot, pad)
+    assert B.autohete_chunk_layout([8, 8], 8) == ([0, 8], 2, 16, 0)
+
+
+def test_chunk_layout_errors():
+    with pytest.raises(B.AutoheteError) as e:
+        B.autohete_chunk_layout([1, 2], 0)
+    assert e.value.status == B.AH_EINVAL
+    with pytest.raises(B.AutoheteError):
+        B.autohete_chunk_layout([2 ** 63, 2 ** 63], 8)          # total overflows 64 bits
+    lib = B.raw()
+    one = (ctypes.c_uint64 * 1)(5)
+    out = ctypes.c_uint64()
+    assert lib.autohete_chunk_layout(one, 1, 8, None, None, ctypes.byref(out), ctypes.byref(out)) == B.AH_EINVAL
+    assert lib.autohete_chunk_layout(None, 1, 8, None, ctypes.byref(out), ctypes.byref(out),
+                                     ctypes.byref(out)) == B.AH_EINVAL
+
+
+def test_null_workspace_is_rejected_without_a_device():
+    lib = B.raw()
+    hp = B.hparams()
+    assert lib.autohete_adamw_step(None, None, 0, B.AH_BF16, 1, ctypes.byref(hp), None) == B.AH_EINVAL
+    assert lib.autohete_grad_prep(None, None, 0, B.AH_BF16, 1.0, 0.0, None, None, None) == B.AH_EINVAL
+    assert lib.autohete_ws_destroy(None) == B.AH_EINVAL
+    assert lib.autohete_ws_create(None, 4) == B.AH_EINVAL
+    assert B.raw().autohete_strerror(B.AH_EALIGN).decode().startswith("device pointer")
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(B.autohete_chunk) == 48 and ctypes.sizeof(B.autohete_hparams) == 28
+
+
+def test_model_data_byte_accounting():
+    # section 2.1: 2 (p16) + 2 (g16) + 12 (fp32 momentum, variance, parameter copy) = 16 B/parameter
+    from paper_2503_01890_amd import modeldata
+    per = {"grad": 2, "param_lp": 2, "master": 4, "exp_avg": 4, "exp_avg_sq": 4}
+    assert set(per) == set(modeldata.STREAMS) and sum(per.values()) == 16

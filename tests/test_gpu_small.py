@@ -1,0 +1,313 @@
+"""GPU parity, unit scale: the HIP path through the C ABI against the CPU oracle, element by
+element, on sizes that span several tiles and ragged tails; error paths; determinism."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from _golden import load_hand_worked
+from _harness import (compare_state, download, oracle_hp, random_state, stream_handle, upload)
+from paper_2503_01890_amd import binding as B
+from paper_2503_01890_amd.modeldata import ModelData, STREAMS
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [u | (m << 4) | (nt << 8) for u in (1, 2, 4) for m in (0, 1) for nt in (0, 1)]
+
+
+def run_gpu(md, ws, dtype, step, hp, extra=0.0, indices=None):
+    arr = md.chunk_array(indices)
+    n = md.n_chunks if indices is None else len(indices)
+    norm, flag = ws.autohete_grad_prep(arr, n, dtype, hp.loss_scale, extra, stream_handle(), want_result=True)
+    ws.autohete_adamw_step(arr, n, dtype, step, hp, stream_handle())
+    torch.cuda.synchronize()
+    return norm, flag
+
+
+def run_oracle(states, dtype, step, hp, extra=0.0):
+    return oracle.full_step(states, dtype, step, oracle_hp(hp), extra)
+
+
+def check_norm(gn, gf, on, of):
+    assert gf == of
+    if not of:
+        assert abs(gn - on) <= 1e-5 * on + 1e-30
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+@pytest.mark.parametrize("n", [1, 3, 4, 7, 8, 9, 1023, 1024, 1025, 2047, 2048, 2049, 4101, 3 * 8192 + 17])
+def test_single_chunk_odd_sizes(dtype, n):
+    rng = np.random.default_rng(n * 2 + dtype)
+    scale = 1.0 if dtype == B.AH_BF16 else 256.0
+    st = random_state(n, dtype, rng, scale=scale)
+    md = ModelData([n])
+    upload(md, 0, st)
+    ws = B.Workspace(4)
+    hp = B.hparams(loss_scale=scale)
+    for step in (1, 2, 3):
+        gn, gf = run_gpu(md, ws, dtype, step, hp)
+        on, of = run_oracle([st], dtype, step, hp)
+        check_norm(gn, gf, on, of)
+        compare_state(download(md, 0), st, "n=%d step=%d" % (n, step))
+    assert np.array_equal(download(md, 0)["grad"], st["grad"])          # gradients are read only
+    ws.close()
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+def test_every_kernel_variant_ragged_multichunk(variant, dtype):
+    rng = np.random.default_rng(variant)
+    numels = [int(x) for x in rng.integers(1, 40_000, 23)] + [8192, 4096, 1, 65536 + 3]
+    states = [random_state(n, dtype, rng) for n in numels]
+    md = ModelData(numels)
+    for i, st in enumerate(states):
+        upload(md, i, st)
+    ws = B.Workspace(len(numels))
+    ws.tune(B.AH_TUNE_STEP_VARIANT, variant)
+    hp = B.hparams(max_grad_norm=0.05)
+    for step in (1, 2):
+        gn, gf = run_gpu(md, ws, dtype, step, hp, extra=1e-4)
+        on, of = run_oracle(states, dtype, step, hp, extra=1e-4)
+        check_norm(gn, gf, on, of)
+        for i, st in enumerate(states):
+            compare_state(download(md, i), st, "variant=%x chunk=%d" % (variant, i))
+    ws.close()
+
+
+def test_hand_worked_examples_through_hip():
+    for name, c in load_hand_worked().items():
+        dtype = B.AH_BF16 if c["dtype"] == "bf16" else B.AH_FP16
+        hp = B.hparams(c["lr"], c["beta1"], c["beta2"], c["eps"], c["weight_decay"], c["max_grad_norm"],
+                       c["loss_scale"])
+        g = torch.tensor(c["grad"], dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        st = dict(grad=g.copy(), param_lp=np.zeros(16, np.uint16), master=c["master"].astype(np.float32),
+                  exp_avg=c["exp_avg"].astype(np.float32), exp_avg_sq=c["exp_avg_sq"].astype(np.float32))
+        md = ModelData([16])
+        upload(md, 0, st)
+        ws = B.Workspace(1)
+        for k in range(1, int(c["steps"]) + 1):
+            run_gpu(md, ws, dtype, int(c["first_step"]) + k - 1, hp)
+            sumsq, norm, flag = ws.autohete_grad_result_get(stream_handle())
+            assert flag == 0 and sumsq == pytest.approx(c["expect_sumsq"], rel=1e-15)
+            got = download(md, 0)
+            for key in ("master", "exp_avg", "exp_avg_sq"):
+                assert np.array_equal(got[key], c["expect_%s_t%d" % (key, k)].astype(np.float32)), (name, key, k)
+            assert np.array_equal(oracle.decode(got["param_lp"], dtype).astype(np.float64),
+                                  c["expect_param_lp_t%d" % k]), (name, k)
+        ws.close()
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+@pytest.mark.parametrize("bad", ["inf", "-inf", "nan"])
+def test_nonfinite_gradient_skips_bit_exactly(dtype, bad):
+    rng = np.random.default_rng(11)
+    numels = [5000, 4096, 777]
+    pat = {B.AH_BF16: {"inf": 0x7F80, "-inf": 0xFF80, "nan": 0x7FC1},
+           B.AH_FP16: {"inf": 0x7C00, "-inf": 0xFC00, "nan": 0x7E01}}[dtype][bad]
+    for chunk, pos in ((0, 0), (0, 4999), (1, 2048), (2, 776)):
+        states = [random_state(n, dtype, rng) for n in numels]
+        states[chunk]["grad"][pos] = pat
+        md = ModelData(numels)
+        for i, st in enumerate(states):
+            upload(md, i, st)
+        ws = B.Workspace(8)
+        gn, gf = run_gpu(md, ws, dtype, 1, B.hparams())
+        on, of = run_oracle(states, dtype, 1, B.hparams())
+        assert gf == 1 and of == 1 and np.isnan(gn)
+        for i, st in enumerate(states):
+            got = download(md, i)
+            for s in STREAMS:
+                assert got[s].tobytes() == st[s].tobytes(), (chunk, pos, i, s)
+        # the next, clean iteration proceeds normally with the same workspace
+        states[chunk]["grad"][pos] = 0
+        upload(md, chunk, dict(grad=states[chunk]["grad"]))
+        gn, gf = run_gpu(md, ws, dtype, 1, B.hparams())
+        on, of = run_oracle(states, dtype, 1, B.hparams())
+        check_norm(gn, gf, on, of)
+        assert gf == 0
+        for i, st in enumerate(states):
+            compare_state(download(md, i), st)
+        ws.close()
+
+
+def test_nonfinite_extra_sumsq_skips():
+    rng = np.random.default_rng(3)
+    st = random_state(3000, B.AH_BF16, rng)
+    md = ModelData([3000])
+    upload(md, 0, st)
+    ws = B.Workspace(1)
+    for extra in (float("inf"), float("nan")):
+        gn, gf = run_gpu(md, ws, B.AH_BF16, 1, B.hparams(), extra=extra)
+        assert gf == 1
+        got = download(md, 0)
+        assert all(got[s].tobytes() == st[s].tobytes() for s in STREAMS)
+    ws.close()
+
+
+def test_partition_invariance_and_subsets():
+    """One optimizer per block: stepping all chunks at once, one by one, or in halves gives
+    bit-identical state; the norm always comes from one prep over all chunks."""
+    rng = np.random.default_rng(21)
+    numels = [9000, 4096, 123, 30000, 8192, 2048]
+    states = [random_state(n, B.AH_BF16, rng) for n in numels]
+    hp = B.hparams(max_grad_norm=0.01)
+    results = []
+    for groups in ([list(range(6))], [[i] for i in range(6)], [[3, 4, 5], [0, 1, 2]], [[5, 0], [2], [4, 1, 3]]):
+        md = ModelData(numels)
+        for i, st in enumerate(states):
+            upload(md, i, st)
+        ws = B.Workspace(6)
+        ws.autohete_grad_prep(md.chunk_array(), 6, B.AH_BF16, 1.0, 0.0, stream_handle())
+        for grp in groups:
+            ws.autohete_adamw_step(md.chunk_array(grp), len(grp), B.AH_BF16, 5, hp, stream_handle())
+        torch.cuda.synchronize()
+        results.append([download(md, i) for i in range(6)])
+        ws.close()
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert all(a[s].tobytes() == b[s].tobytes() for s in STREAMS)
+    ora = [{k: v.copy() for k, v in st.items()} for st in states]
+    oracle.full_step(ora, oracle.BF16, 5, oracle_hp(hp))
+    for a, o in zip(results[0], ora):
+        compare_state(a, o)
+
+
+def test_result_set_steps_with_host_supplied_norm():
+    rng = np.random.default_rng(22)
+    st = random_state(10_000, B.AH_BF16, rng)
+    md = ModelData([10_000])
+    upload(md, 0, st)
+    ws = B.Workspace(1)
+    hp = B.hparams(max_grad_norm=0.5)
+    ws.autohete_grad_result_set(4.0, 0, stream_handle())            # norm 2 -> coef 0.25 (minus guard)
+    ws.autohete_adamw_step(md.chunk_array(), 1, B.AH_BF16, 2, hp, stream_handle())
+    torch.cuda.synchronize()
+    assert ws.autohete_grad_result_get(stream_handle()) == (4.0, 2.0, 0)
+    oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], oracle.BF16, 2,
+                       oracle_hp(hp), 2.0, 0)
+    compare_state(download(md, 0), st)
+    ws.autohete_grad_result_set(1.0, 1, stream_handle())            # flagged: step must not touch anything
+    ws.autohete_adamw_step(md.chunk_array(), 1, B.AH_BF16, 3, hp, stream_handle())
+    torch.cuda.synchronize()
+    compare_state(download(md, 0), st)
+    ws.close()
+
+
+def test_run_to_run_determinism_and_grid_independence():
+    rng = np.random.default_rng(23)
+    numels = [1 << 20, 333_333, 1 << 18]
+    states = [random_state(n, B.AH_FP16, rng, scale=1024.0) for n in numels]
+    hp = B.hparams(loss_scale=1024.0)
+    outs, sums = [], []
+    for prep_blocks in (0, 0, 1, 7, 1000):
+        md = ModelData(numels)
+        for i, st in enumerate(states):
+            upload(md, i, st)
+        ws = B.Workspace(3)
+        ws.tune(B.AH_TUNE_PREP_BLOCKS, prep_blocks)
+        run_gpu(md, ws, B.AH_FP16, 1, hp)
+        sums.append(ws.autohete_grad_result_get(stream_handle())[0])
+        outs.append([download(md, i) for i in range(3)])
+        ws.close()
+    assert sums[0] == sums[1]                                           # same launch: bit-identical
+    for a, b in zip(outs[0], outs[1]):
+        assert all(a[s].tobytes() == b[s].tobytes() for s in STREAMS)
+    for s in sums[2:]:
+        assert abs(s - sums[0]) <= 1e-12 * sums[0]                      # any grid: same sum to fp64 rounding
+    ref = sum(float(np.sum((oracle.decode(st["grad"], oracle.FP16).astype(np.float64) / 1024.0) ** 2)) for st in states)
+    assert abs(sums[0] - ref) <= 1e-12 * ref
+
+
+def test_empty_chunk_list_and_extra_only():
+    ws = B.Workspace(2)
+    arr = B.chunk_array([])
+    assert ws.autohete_grad_prep(arr, 0, B.AH_BF16, 1.0, 9.0, stream_handle(), want_result=True) == (3.0, 0)
+    ws.autohete_adamw_step(arr, 0, B.AH_BF16, 1, B.hparams(), stream_handle())
+    torch.cuda.synchronize()
+    ws.close()
+
+
+def test_error_codes():
+    md = ModelData([4096, 4096])
+    md.zero_()
+    ws = B.Workspace(2)
+    lib, h = B.raw(), ws._h
+    hp = B.hparams()
+    good = md.chunk_array()
+    s = ctypes.c_void_p(stream_handle())
+
+    def step(arr, n, dtype=B.AH_BF16, t=1, hp_=hp):
+        return lib.autohete_adamw_step(h, arr, n, dtype, t, ctypes.byref(hp_), s)
+
+    assert step(good, 2) == B.AH_OK
+    assert step(good, 2, t=0) == B.AH_EINVAL
+    assert step(good, 2, dtype=7) == B.AH_EINVAL
+    assert step(good, 3) == B.AH_ENOMEM
+    assert step(None, 2) == B.AH_EINVAL
+    for bad in (B.hparams(beta1=1.0), B.hparams(beta2=-0.1), B.hparams(lr=float("nan")), B.hparams(loss_scale=0.0),
+                B.hparams(eps=-1.0), B.hparams(weight_decay=float("inf"))):
+        assert step(good, 2, hp_=bad) == B.AH_EINVAL
+    t = list(md.chunk_tuple(0))
+    for field in range(5):
+        mis = list(t)
+        mis[field] += 2
+        assert step(B.chunk_array([mis]), 1) == B.AH_EALIGN, field
+        nul = list(t)
+        nul[field] = None
+        assert step(B.chunk_array([nul]), 1) == B.AH_EINVAL, field
+    zero = list(t)
+    zero[5] = 0
+    assert step(B.chunk_array([zero]), 1) == B.AH_EINVAL
+    assert lib.autohete_grad_prep(h, good, 2, B.AH_BF16, ctypes.c_float(0.0), 0.0, s, None, None) == B.AH_EINVAL
+    assert lib.autohete_grad_prep(h, good, 2, 9, ctypes.c_float(1.0), 0.0, s, None, None) == B.AH_EINVAL
+    mis = list(t)
+    mis[0] += 2
+    assert lib.autohete_grad_prep(h, B.chunk_array([mis]), 1, B.AH_BF16, ctypes.c_float(1.0), 0.0, s, None,
+                                  None) == B.AH_EALIGN
+    assert lib.autohete_ws_tune(h, 99, 1) == B.AH_EINVAL
+    assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_VARIANT, 3) == B.AH_EINVAL
+    torch.cuda.synchronize()
+    got = download(md, 0)
+    assert not got["exp_avg"].any()                                   # rejected calls launched nothing harmful
+    ws.close()
+
+
+def test_padding_stays_zero_and_checkpoint_resume():
+    """Zero padding stays +0 in every stream; 6 steps == 3 steps, state round-trip via host, 3 steps."""
+    rng = np.random.default_rng(31)
+    n, pad = 50_000, 1234
+    st = random_state(n, B.AH_BF16, rng)
+    for k in st:
+        st[k][-pad:] = 0
+    grads = [random_state(n, B.AH_BF16, rng)["grad"] for _ in range(6)]
+    for g in grads:
+        g[-pad:] = 0
+    hp = B.hparams()
+
+    def run(md, ws, lo, hi):
+        for t in range(lo, hi):
+            upload(md, 0, dict(grad=grads[t - 1]))
+            run_gpu(md, ws, B.AH_BF16, t, hp)
+
+    md = ModelData([n])
+    upload(md, 0, st)
+    ws = B.Workspace(1)
+    run(md, ws, 1, 7)
+    straight = download(md, 0)
+    for s in STREAMS:
+        assert not straight[s][-pad:].view(np.uint8).any(), s
+    md2 = ModelData([n])
+    upload(md2, 0, st)
+    ws2 = B.Workspace(1)
+    run(md2, ws2, 1, 4)
+    saved = download(md2, 0)
+    ws2.close()
+    md3 = ModelData([n])
+    upload(md3, 0, saved)
+    ws3 = B.Workspace(1)
+    run(md3, ws3, 4, 7)
+    resumed = download(md3, 0)
+    assert all(straight[s].tobytes() == resumed[s].tobytes() for s in STREAMS)
+    ws.close(), ws3.close()
