@@ -120,8 +120,8 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
 
 /*
  * The update (rule at the top of this file) over the given chunks in one fused pass:
- * 14 bytes read and 14 bytes written per element; the states are touched once
- * (appendix, "accessed only once for optimizer updates").  It consumes the workspace's
+ * 14 bytes read and 14 bytes written per element; each optimizer state is read once and
+ * written once per update (the paper's appendix on memory allocation states the same).  It consumes the workspace's
  * device-side result, so it must follow an autohete_grad_prep (or
  * autohete_grad_result_set) on the same stream.  If the skip flag is set the kernel
  * exits before its first load and every stream is left bit-identical; the caller should
@@ -152,9 +152,13 @@ int autohete_grad_result_set(autohete_ws *ws, double sumsq, uint32_t found_inf, 
  * norm (last bits of S).
  */
 enum {
-    AH_TUNE_STEP_BLOCKS = 0, /* resident thread blocks of the step kernel; 0 = default      */
-    AH_TUNE_PREP_BLOCKS = 1, /* thread blocks of the prep kernel; 0 = default               */
-    AH_TUNE_STEP_VARIANT = 2 /* kernel variant index, see autohete_kernels.hip; 0 = default */
+    AH_TUNE_STEP_BLOCKS_PER_CU = 0, /* cap on step-kernel blocks resident per CU (1..64; 64 =
+                                       no cap); 0 = default                                    */
+    AH_TUNE_PREP_BLOCKS = 1,        /* thread blocks of the prep kernel; 0 = default           */
+    AH_TUNE_STEP_VARIANT = 2        /* step-kernel variant: elements per lane (1, 2, 4)
+                                       | mode << 4 (0 = fp64 Newton root/quotient, 1 = fp64
+                                       correctly rounded) | (threads per block / 64) << 8;
+                                       0 = default                                             */
 };
 int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value);
 

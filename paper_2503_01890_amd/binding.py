@@ -12,7 +12,12 @@ LIB_PATH = os.path.join(_HERE, "libautohete.so")
 
 AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP = 0, -1, -2, -3, -4
 AH_BF16, AH_FP16 = 0, 1
-AH_TUNE_STEP_BLOCKS, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT = 0, 1, 2
+AH_TUNE_STEP_BLOCKS_PER_CU, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT = 0, 1, 2
+
+
+def step_variant(vec=4, block=64, mode=0):
+    """Encode a value for AH_TUNE_STEP_VARIANT."""
+    return vec | (mode << 4) | ((block // 64) << 8)
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libautohete.so is not built (%s): run __graft_entry__.build() or "

@@ -7,6 +7,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -24,71 +25,68 @@ struct autohete_ws {
     DevChunk *d_tab[2] = {nullptr, nullptr};
     DevChunk *h_stage[2] = {nullptr, nullptr}; /* pinned staging for the async upload */
     std::vector<DevChunk> h_last[2];            /* what d_tab holds */
-    uint64_t last_tiles[2] = {0, 0};
     hipEvent_t staged[2] = {nullptr, nullptr};  /* upload from h_stage has completed */
     bool staged_pending[2] = {false, false};
     double *d_partials = nullptr;
     uint32_t *d_ticket = nullptr;
     GradResult *d_res = nullptr;
     GradResult *h_res = nullptr;                /* pinned read-back */
-    int64_t tune_step_blocks = 0, tune_prep_blocks = 0, tune_step_variant = 0;
-    int occ_cache[2][64];                       /* resident blocks/CU per dtype and variant */
-    int prep_occ[2] = {0, 0};
+    int64_t tune_step_blocks_per_cu = 0, tune_prep_blocks = 0, tune_step_variant = 0;
+    int prep_occ[2] = {0, 0};                   /* resident prep blocks/CU per dtype */
+    size_t lds_per_cu = 0;
+    /* launch groups of the current step table: rows [first, first+rows) share grid_x */
+    struct Group { uint32_t first, rows; uint64_t max_tiles; };
+    std::vector<Group> step_groups;
 };
 
 namespace {
 
-/* Default variant: 2x unroll, fp64 moments with fp32 root/quotient, non-temporal accesses.
- * Encoding of AH_TUNE_STEP_VARIANT: unroll | mode << 4 | nt << 8. */
-constexpr int64_t kDefaultVariant = 2 | (0 << 4) | (1 << 8);
+/* Encoding of AH_TUNE_STEP_VARIANT: vec | mode << 4 | (block / 64) << 8.
+ * Default: 4 elements per lane, one wavefront per block, Newton fp64, at most 10 blocks per CU. */
+constexpr int64_t kDefaultVariant = 4 | (0 << 4) | (1 << 8);
+constexpr int kDefaultBlocksPerCu = 10;
 
 bool decode_variant(int64_t v, ah::StepVariant *out)
 {
     if (v == 0) v = kDefaultVariant;
-    ah::StepVariant s{(int)(v & 0xF), (int)((v >> 4) & 0xF), (int)((v >> 8) & 0xF)};
-    if (!(s.unroll == 1 || s.unroll == 2 || s.unroll == 4) || s.mode > 1 || s.nt > 1 || (v >> 12)) return false;
+    ah::StepVariant s{(int)(v & 0xF), (int)((v >> 8) & 0xFF) * 64, (int)((v >> 4) & 0xF)};
+    if ((v >> 16) || !ah::step_variant_valid(s)) return false;
     *out = s;
     return true;
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-/* Validate the caller's chunks and build the device table for tiles of tile_elems.
- * need_all: the step needs all five streams, the prep only the gradients. */
-int build_table(autohete_ws *ws, int slot, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
-                bool need_all, hipStream_t stream, uint64_t *total_tiles)
+int validate_chunk(const autohete_chunk &c, bool need_all)
 {
-    if (n > ws->max_chunks) return AH_ENOMEM;
-    if (n && !chunks) return AH_EINVAL;
-    std::vector<DevChunk> tab(n + 1);
-    uint64_t tiles = 0;
-    for (uint64_t i = 0; i < n; ++i) {
-        const autohete_chunk &c = chunks[i];
-        if (c.numel == 0 || !c.grad) return AH_EINVAL;
-        if (need_all && (!c.param_lp || !c.master || !c.exp_avg || !c.exp_avg_sq)) return AH_EINVAL;
-        if (!aligned16(c.grad)) return AH_EALIGN;
-        if (need_all && !(aligned16(c.param_lp) && aligned16(c.master) && aligned16(c.exp_avg) &&
-                          aligned16(c.exp_avg_sq)))
-            return AH_EALIGN;
-        DevChunk &d = tab[i];
-        d.grad = static_cast<const uint16_t *>(c.grad);
-        d.param_lp = static_cast<uint16_t *>(c.param_lp);
-        d.master = c.master;
-        d.exp_avg = c.exp_avg;
-        d.exp_avg_sq = c.exp_avg_sq;
-        d.numel = c.numel;
-        d.tile_begin = tiles;
-        d.reserved = 0;
-        tiles += (c.numel + tile_elems - 1) / tile_elems;
-    }
-    memset(&tab[n], 0, sizeof(DevChunk));
-    tab[n].tile_begin = tiles; /* sentinel */
-    *total_tiles = tiles;
+    if (c.numel == 0 || !c.grad) return AH_EINVAL;
+    if (need_all && (!c.param_lp || !c.master || !c.exp_avg || !c.exp_avg_sq)) return AH_EINVAL;
+    if (!aligned16(c.grad)) return AH_EALIGN;
+    if (need_all && !(aligned16(c.param_lp) && aligned16(c.master) && aligned16(c.exp_avg) &&
+                      aligned16(c.exp_avg_sq)))
+        return AH_EALIGN;
+    return AH_OK;
+}
 
+void fill_row(DevChunk &d, const autohete_chunk &c, uint64_t tile_begin)
+{
+    d.grad = static_cast<const uint16_t *>(c.grad);
+    d.param_lp = static_cast<uint16_t *>(c.param_lp);
+    d.master = c.master;
+    d.exp_avg = c.exp_avg;
+    d.exp_avg_sq = c.exp_avg_sq;
+    d.numel = c.numel;
+    d.tile_begin = tile_begin;
+    d.reserved = 0;
+}
+
+/* Upload `tab` into table slot `slot` unless the device copy already holds exactly that. */
+int upload_table(autohete_ws *ws, int slot, std::vector<DevChunk> &tab, hipStream_t stream, bool *changed)
+{
     std::vector<DevChunk> &last = ws->h_last[slot];
-    if (last.size() == tab.size() && memcmp(last.data(), tab.data(), tab.size() * sizeof(DevChunk)) == 0)
-        return AH_OK; /* device copy is current */
-
+    *changed = !(last.size() == tab.size() &&
+                 memcmp(last.data(), tab.data(), tab.size() * sizeof(DevChunk)) == 0);
+    if (!*changed) return AH_OK;
     if (ws->staged_pending[slot]) { /* the previous upload may still be reading the staging buffer */
         if (hipEventSynchronize(ws->staged[slot]) != hipSuccess) return AH_EHIP;
         ws->staged_pending[slot] = false;
@@ -100,6 +98,79 @@ int build_table(autohete_ws *ws, int slot, const autohete_chunk *chunks, uint64_
     if (hipEventRecord(ws->staged[slot], stream) != hipSuccess) return AH_EHIP;
     ws->staged_pending[slot] = true;
     last.swap(tab);
+    return AH_OK;
+}
+
+/* Table of the prep kernel: rows in the caller's order, each with the index of its first tile;
+ * row n is a sentinel holding the total tile count. */
+int build_prep_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
+                     hipStream_t stream, uint64_t *total_tiles)
+{
+    if (n > ws->max_chunks) return AH_ENOMEM;
+    if (n && !chunks) return AH_EINVAL;
+    std::vector<DevChunk> tab(n + 1);
+    uint64_t tiles = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        int rc = validate_chunk(chunks[i], false);
+        if (rc != AH_OK) return rc;
+        fill_row(tab[i], chunks[i], tiles);
+        tiles += (chunks[i].numel + tile_elems - 1) / tile_elems;
+    }
+    memset(&tab[n], 0, sizeof(DevChunk));
+    tab[n].tile_begin = tiles;
+    *total_tiles = tiles;
+    bool changed;
+    return upload_table(ws, 0, tab, stream, &changed);
+}
+
+/* Table of the step kernel: one row per chunk, rows grouped by ceil(log2(tile count)) so that
+ * each group can be launched as a 2-D grid (x = tile, y = row) in which at most half of the
+ * blocks fall beyond the end of their chunk.  Equal-sized chunks form a single group. */
+int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
+                     hipStream_t stream)
+{
+    if (n > ws->max_chunks) return AH_ENOMEM;
+    if (n && !chunks) return AH_EINVAL;
+    std::vector<uint64_t> tiles(n);
+    std::vector<uint32_t> bucket(n);
+    uint32_t count[65] = {0};
+    for (uint64_t i = 0; i < n; ++i) {
+        int rc = validate_chunk(chunks[i], true);
+        if (rc != AH_OK) return rc;
+        tiles[i] = (chunks[i].numel + tile_elems - 1) / tile_elems;
+        if (tiles[i] > 0x7FFFFFFFull) return AH_EINVAL; /* grid.x limit: chunk too large */
+        bucket[i] = tiles[i] <= 1 ? 0 : 64 - (uint32_t)__builtin_clzll(tiles[i] - 1);
+        ++count[bucket[i]];
+    }
+    uint32_t start[65];
+    uint32_t run = 0;
+    for (int b = 0; b < 65; ++b) {
+        start[b] = run;
+        run += count[b];
+    }
+    std::vector<DevChunk> tab(n + 1);
+    std::vector<uint64_t> row_tiles(n);
+    uint32_t fillpos[65];
+    memcpy(fillpos, start, sizeof(start));
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint32_t r = fillpos[bucket[i]]++;
+        fill_row(tab[r], chunks[i], 0);
+        row_tiles[r] = tiles[i];
+    }
+    memset(&tab[n], 0, sizeof(DevChunk));
+    std::vector<autohete_ws::Group> groups;
+    for (int b = 0; b < 65; ++b) {
+        for (uint32_t first = start[b]; first < start[b] + count[b]; first += 65535u) {
+            const uint32_t rows = std::min<uint32_t>(65535u, start[b] + count[b] - first);
+            uint64_t mx = 0;
+            for (uint32_t r = first; r < first + rows; ++r) mx = std::max(mx, row_tiles[r]);
+            groups.push_back({first, rows, mx});
+        }
+    }
+    bool changed;
+    int rc = upload_table(ws, 1, tab, stream, &changed);
+    if (rc != AH_OK) return rc;
+    ws->step_groups.swap(groups);
     return AH_OK;
 }
 
@@ -159,10 +230,12 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
     autohete_ws *ws = new (std::nothrow) autohete_ws;
     if (!ws) return AH_ENOMEM;
     ws->max_chunks = max_chunks;
-    memset(ws->occ_cache, 0, sizeof(ws->occ_cache));
     hipDeviceProp_t prop;
     bool ok = hipGetDevice(&ws->device) == hipSuccess && hipGetDeviceProperties(&prop, ws->device) == hipSuccess;
-    if (ok) ws->n_cu = prop.multiProcessorCount;
+    if (ok) {
+        ws->n_cu = prop.multiProcessorCount;
+        ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+    }
     const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
     for (int s = 0; ok && s < 2; ++s) {
         ok = hipMalloc(&ws->d_tab[s], tab_bytes) == hipSuccess &&
@@ -207,9 +280,9 @@ int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value)
 {
     if (!ws || value < 0) return AH_EINVAL;
     switch (knob) {
-        case AH_TUNE_STEP_BLOCKS:
-            if (value > (1 << 30)) return AH_EINVAL;
-            ws->tune_step_blocks = value;
+        case AH_TUNE_STEP_BLOCKS_PER_CU:
+            if (value > 64) return AH_EINVAL;
+            ws->tune_step_blocks_per_cu = value;
             return AH_OK;
         case AH_TUNE_PREP_BLOCKS:
             if (value > ah::kMaxPartials) return AH_EINVAL;
@@ -246,7 +319,7 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     if (!g.ok) return AH_EHIP;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     uint64_t tiles = 0;
-    int rc = build_table(ws, 0, chunks, n_chunks, ah::prep_tile_elems(), false, stream, &tiles);
+    int rc = build_prep_table(ws, chunks, n_chunks, ah::prep_tile_elems(), stream, &tiles);
     if (rc != AH_OK) return rc;
 
     int &occ = ws->prep_occ[lowp_dtype];
@@ -277,10 +350,9 @@ int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t 
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     ah::StepVariant var;
     if (!decode_variant(ws->tune_step_variant, &var)) return AH_EINVAL;
-    uint64_t tiles = 0;
-    int rc = build_table(ws, 1, chunks, n_chunks, ah::step_tile_elems(var.unroll), true, stream, &tiles);
+    int rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block), stream);
     if (rc != AH_OK) return rc;
-    if (tiles == 0) return AH_OK;
+    if (n_chunks == 0) return AH_OK;
 
     /* Per-launch constants, fp64 from the fp32 hyper-parameters. */
     ah::StepConsts k;
@@ -298,15 +370,20 @@ int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t 
     k.eps = (double)hp->eps;
     k.wd = (double)hp->weight_decay;
 
-    const int vidx = (var.unroll == 1 ? 0 : var.unroll == 2 ? 1 : 2) + 3 * var.mode + 6 * var.nt;
-    int &occ = ws->occ_cache[lowp_dtype][vidx];
-    if (occ == 0) occ = ah::step_occupancy(lowp_dtype, var);
-    if (occ <= 0) return AH_EHIP;
-    uint64_t blocks = ws->tune_step_blocks ? (uint64_t)ws->tune_step_blocks : (uint64_t)ws->n_cu * occ;
-    if (blocks > tiles) blocks = tiles;
-    if (ah::launch_step(lowp_dtype, var, (unsigned)blocks, stream, ws->d_tab[1], (uint32_t)n_chunks, tiles,
-                        ws->d_res, k) != hipSuccess)
-        return AH_EHIP;
+    /* Cap on resident blocks per CU, enforced through the dynamic LDS request: the launcher asks
+     * for 1/cap of a CU's LDS per block (the kernel itself uses none). */
+    const int64_t cap = ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu : kDefaultBlocksPerCu;
+    unsigned lds = 0;
+    if (cap < 64 && ws->lds_per_cu) {
+        size_t want = ws->lds_per_cu / (size_t)cap;
+        want = want > 1024 ? want - 512 : want;          /* stay clear of allocation-granule rounding */
+        lds = (unsigned)std::min<size_t>(want, 64 * 1024);
+    }
+    for (const autohete_ws::Group &grp : ws->step_groups) {
+        if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
+                            ws->d_tab[1] + grp.first, ws->d_res, k) != hipSuccess)
+            return AH_EHIP;
+    }
     return AH_OK;
 }
 

@@ -7,7 +7,6 @@
 namespace ah {
 
 constexpr int kThreads = 256;        /* 4 wavefronts of 64 */
-constexpr int kStepVec = 4;          /* elements per lane per load group in the step kernel */
 constexpr int kPrepVec = 8;          /* elements per lane per load in the prep kernel */
 constexpr int kMaxPartials = 16384;  /* upper bound on prep blocks */
 
@@ -28,7 +27,8 @@ static_assert(sizeof(DevChunk) == 64, "DevChunk is one 64-byte line");
 /* Result of the gradient preparation, kept in device memory between the two kernels. */
 struct GradResult {
     double sumsq;       /* extra_sumsq + sum (grad/loss_scale)^2 */
-    float norm;         /* sqrt(sumsq) rounded to fp32; NaN when found_inf */
+    double norm_d;      /* sqrt(sumsq); NaN when found_inf */
+    float norm;         /* norm_d rounded to fp32 */
     uint32_t found_inf; /* 1: skip the step */
 };
 
@@ -43,20 +43,21 @@ struct StepConsts {
     double lr, eps, wd;
 };
 
-/* Step-kernel variants: unroll U in {1,2,4}; mode 0 = fp64 moments, fp32 root and quotient;
- * mode 1 = everything in fp64; nt = non-temporal loads and stores. */
-struct StepVariant { int unroll, mode, nt; };
+/* Step-kernel variants: vec = elements per lane (1, 2, 4), block = threads per block,
+ * mode 0 = fp64 with Newton root/quotient, mode 1 = fp64 with correctly rounded root/quotient. */
+struct StepVariant { int vec, block, mode; };
+bool step_variant_valid(StepVariant s);
 
-hipError_t launch_step(int dtype, StepVariant var, unsigned blocks, hipStream_t stream, const DevChunk *tab,
-                       uint32_t n_chunks, uint64_t total_tiles, const GradResult *res, const StepConsts &k);
+/* grid_x tiles of vec*block elements for each of grid_y table rows; lds_bytes of dynamic LDS
+ * per block caps the blocks resident per CU. */
+hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
+                       hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k);
 hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const DevChunk *tab, uint32_t n_chunks,
                        uint64_t total_tiles, double inv_scale, double extra_sumsq, double *partials,
                        uint32_t *ticket, GradResult *res);
 hipError_t launch_set_result(hipStream_t stream, GradResult *res, double sumsq, uint32_t found_inf);
-int step_occupancy(int dtype, StepVariant var);   /* resident blocks per CU, <= 0 on error */
-int prep_occupancy(int dtype);
+int prep_occupancy(int dtype);   /* resident blocks per CU, <= 0 on error */
 
-inline uint32_t step_tile_elems(int unroll) { return (uint32_t)(kThreads * kStepVec * unroll); }
 constexpr int kPrepUnroll = 2;
 inline uint32_t prep_tile_elems() { return (uint32_t)(kThreads * kPrepVec * kPrepUnroll); }
 

@@ -21,6 +21,7 @@
 namespace ah {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -84,6 +85,9 @@ __device__ __forceinline__ void unpack2(uint32_t w, float &lo, float &hi)
 /* ------------------------------------------------------------------------------------- */
 /* One element of the update.  Each written operation is one IEEE fp64 operation (no      */
 /* contraction), in the order of the rule in autohete.h.                                  */
+/* MODE 0: root and quotient by Newton iteration in fp64 from the hardware's reciprocal   */
+/*         (square-root) estimates -- a few ulp of fp64, far below one fp32 rounding.      */
+/* MODE 1: correctly rounded fp64 root and divisions (reference variant, more ALU work).   */
 /* ------------------------------------------------------------------------------------- */
 template <int MODE>
 __device__ __forceinline__ void adamw_elem(float gf, float &p, float &m, float &v, const StepConsts &k,
@@ -98,11 +102,20 @@ __device__ __forceinline__ void adamw_elem(float gf, float &p, float &m, float &
     if constexpr (MODE == 1) {
         upd = (mn / k.bc1) / (sqrt(vn / k.bc2) + k.eps);
     } else {
-        /* The quotient only has to be good to ~1e-7 relative: it is scaled by lr before it
-         * meets p.  fp32 root and division are correctly rounded. */
-        const float mh = (float)(mn * k.rbc1);
-        const float vh = (float)(vn * k.rbc2);
-        upd = (double)(mh / (sqrtf(vh) + (float)k.eps));
+        const double vh = vn * k.rbc2, mh = mn * k.rbc1;
+        /* sqrt(vh): y ~ 1/sqrt(vh) from v_rsq_f64 (about 2^-23 relative), s = vh*y, then two
+         * steps s <- s + (vh - s*s) * y/2, each squaring the error.  vh = 0 gives s = 0. */
+        const double y = vh > 0.0 ? __builtin_amdgcn_rsq(vh) : 0.0;
+        const double hy = 0.5 * y;
+        double s = vh * y;
+        s = __builtin_fma(__builtin_fma(-s, s, vh), hy, s);
+        s = __builtin_fma(__builtin_fma(-s, s, vh), hy, s);
+        /* 1/den: q from v_rcp_f64, two steps q <- q + q*(1 - den*q). */
+        const double den = s + k.eps;
+        double q = __builtin_amdgcn_rcp(den);
+        q = __builtin_fma(q, __builtin_fma(-den, q, 1.0), q);
+        q = __builtin_fma(q, __builtin_fma(-den, q, 1.0), q);
+        upd = mh * q;
     }
     const double pn = pd - k.lr * (upd + k.wd * pd);
     m = (float)mn;
@@ -110,91 +123,110 @@ __device__ __forceinline__ void adamw_elem(float gf, float &p, float &m, float &
     p = (float)pn;
 }
 
-template <int DT, int U, int MODE, bool NT>
-__device__ __forceinline__ void step_full_tile(const DevChunk &ch, uint64_t e0, const StepConsts &k, double coef)
+template <int VEC> struct VecTypes;
+template <> struct VecTypes<4> { typedef f32x4 f32; typedef u32x2 lowp; };
+template <> struct VecTypes<2> { typedef f32x2 f32; typedef uint32_t lowp; };
+template <> struct VecTypes<1> { typedef float f32; typedef uint16_t lowp; };
+
+template <int DT, int VEC>
+__device__ __forceinline__ void unpack_lowp(typename VecTypes<VEC>::lowp raw, float *gf)
 {
-    const uint32_t lane_off = threadIdx.x * kStepVec;
-    u32x2 g[U];
-    f32x4 p[U], m[U], v[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint64_t off = e0 + (uint64_t)u * (kThreads * kStepVec) + lane_off;
-        g[u] = ld<NT>(gptr<u32x2>(ch.grad + off));
-        p[u] = ld<NT>(gptr<f32x4>((const float *)ch.master + off));
-        m[u] = ld<NT>(gptr<f32x4>((const float *)ch.exp_avg + off));
-        v[u] = ld<NT>(gptr<f32x4>((const float *)ch.exp_avg_sq + off));
+    if constexpr (VEC == 4) {
+        unpack2<DT>(raw.x, gf[0], gf[1]);
+        unpack2<DT>(raw.y, gf[2], gf[3]);
+    } else if constexpr (VEC == 2) {
+        unpack2<DT>(raw, gf[0], gf[1]);
+    } else {
+        gf[0] = lowp_to_f32<DT>(raw);
     }
-    /* Keep every load of the tile ahead of the arithmetic: 4*U requests in flight per lane. */
-    __builtin_amdgcn_sched_barrier(0);
+}
+template <int DT, int VEC>
+__device__ __forceinline__ typename VecTypes<VEC>::lowp pack_lowp(const float *pp)
+{
+    if constexpr (VEC == 4) {
+        u32x2 o;
+        o.x = f32_to_lowp<DT>(pp[0]) | (f32_to_lowp<DT>(pp[1]) << 16);
+        o.y = f32_to_lowp<DT>(pp[2]) | (f32_to_lowp<DT>(pp[3]) << 16);
+        return o;
+    } else if constexpr (VEC == 2) {
+        return f32_to_lowp<DT>(pp[0]) | (f32_to_lowp<DT>(pp[1]) << 16);
+    } else {
+        return (uint16_t)f32_to_lowp<DT>(pp[0]);
+    }
+}
+template <int VEC>
+__device__ __forceinline__ void split(const typename VecTypes<VEC>::f32 &x, float *out)
+{
+    if constexpr (VEC == 1) out[0] = x;
+    else
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint64_t off = e0 + (uint64_t)u * (kThreads * kStepVec) + lane_off;
-        float gf[4], pp[4], mm[4], vv[4];
-        unpack2<DT>(g[u].x, gf[0], gf[1]);
-        unpack2<DT>(g[u].y, gf[2], gf[3]);
+        for (int j = 0; j < VEC; ++j) out[j] = x[j];
+}
+template <int VEC>
+__device__ __forceinline__ typename VecTypes<VEC>::f32 join(const float *in)
+{
+    if constexpr (VEC == 1) return in[0];
+    else {
+        typename VecTypes<VEC>::f32 r;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            pp[j] = p[u][j];
-            mm[j] = m[u][j];
-            vv[j] = v[u][j];
-            adamw_elem<MODE>(gf[j], pp[j], mm[j], vv[j], k, coef);
-        }
-        u32x2 o16;
-        o16.x = f32_to_lowp<DT>(pp[0]) | (f32_to_lowp<DT>(pp[1]) << 16);
-        o16.y = f32_to_lowp<DT>(pp[2]) | (f32_to_lowp<DT>(pp[3]) << 16);
-        f32x4 po = {pp[0], pp[1], pp[2], pp[3]}, mo = {mm[0], mm[1], mm[2], mm[3]},
-              vo = {vv[0], vv[1], vv[2], vv[3]};
-        st<NT>(gptr<f32x4>(ch.master + off), po);
-        st<NT>(gptr<f32x4>(ch.exp_avg + off), mo);
-        st<NT>(gptr<f32x4>(ch.exp_avg_sq + off), vo);
-        st<NT>(gptr<u32x2>(ch.param_lp + off), o16);
+        for (int j = 0; j < VEC; ++j) r[j] = in[j];
+        return r;
     }
 }
 
-/* The last, partial tile of a chunk: element-wise, bounds-checked. */
-template <int DT, int U, int MODE>
-__device__ __forceinline__ void step_tail_tile(const DevChunk &ch, uint64_t e0, const StepConsts &k, double coef)
-{
-    const uint64_t full = e0 + (uint64_t)U * (kThreads * kStepVec);
-    const uint64_t end = full < ch.numel ? full : ch.numel;
-    AH_GLOBAL float *master = gptr<float>(ch.master), *exp_avg = gptr<float>(ch.exp_avg),
-                    *exp_avg_sq = gptr<float>(ch.exp_avg_sq);
-    const AH_GLOBAL uint16_t *grad = gptr<uint16_t>(ch.grad);
-    AH_GLOBAL uint16_t *param_lp = gptr<uint16_t>(ch.param_lp);
-    for (uint64_t i = e0 + threadIdx.x; i < end; i += kThreads) {
-        float p = master[i], m = exp_avg[i], v = exp_avg_sq[i];
-        adamw_elem<MODE>(lowp_to_f32<DT>(grad[i]), p, m, v, k, coef);
-        master[i] = p;
-        exp_avg[i] = m;
-        exp_avg_sq[i] = v;
-        param_lp[i] = (uint16_t)f32_to_lowp<DT>(p);
-    }
-}
-
-template <int DT, int U, int MODE, bool NT>
-__global__ void __launch_bounds__(kThreads)
-adamw_step_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t total_tiles,
-                  const GradResult *__restrict__ res, StepConsts k)
+/*
+ * The update kernel.  No loop: one thread block per tile of BS*VEC elements, blockIdx.y = the
+ * chunk (row of the table), blockIdx.x = the tile inside it.  The hardware dispatches blocks
+ * in order, so the blocks in flight always cover one narrow, advancing window of each of the
+ * five streams -- which is what keeps HBM pages open; a persistent grid-stride loop lets waves
+ * drift apart and measured 10-20 % slower.  The number of blocks resident per CU is capped by
+ * the launcher (through the dynamic LDS size): about 30 KB of loads in flight per CU is the
+ * measured optimum, more in flight widens the window and costs bandwidth.
+ * All accesses are non-temporal: every byte is touched exactly once per step.
+ */
+template <int DT, int VEC, int BS, int MODE>
+__global__ void __launch_bounds__(BS)
+adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k)
 {
     /* Skip-on-overflow: leave before the first load; no stream is touched. */
     if (res->found_inf) return;
+    const DevChunk ch = tab[blockIdx.y];
+    const uint64_t off = (uint64_t)blockIdx.x * (BS * VEC) + threadIdx.x * VEC;
+    if (off >= ch.numel) return; /* grid.x is the largest tile count of the launch group */
     double coef = 1.0;
     if (k.max_norm > 0.0) {
-        const double c = k.max_norm / (sqrt(res->sumsq) + 1e-6);
+        const double c = k.max_norm / (res->norm_d + 1e-6);
         coef = c < 1.0 ? c : 1.0;
     }
-    constexpr uint32_t kTile = kThreads * kStepVec * U;
-    uint32_t c = 0;
-    /* Grid-stride over tiles: at any moment the resident blocks cover one contiguous window
-     * of every stream.  The chunk cursor only moves forward (wave-uniform, scalar). */
-    for (uint64_t w = blockIdx.x; w < total_tiles; w += gridDim.x) {
-        while (w >= tab[c + 1].tile_begin) ++c; /* sentinel entry n_chunks ends the search */
-        const DevChunk ch = tab[c];
-        const uint64_t e0 = (w - ch.tile_begin) * kTile;
-        if (e0 + kTile <= ch.numel) step_full_tile<DT, U, MODE, NT>(ch, e0, k, coef);
-        else step_tail_tile<DT, U, MODE>(ch, e0, k, coef);
+    typedef typename VecTypes<VEC>::f32 fvec;
+    typedef typename VecTypes<VEC>::lowp hvec;
+    if (off + VEC <= ch.numel) {
+        const hvec graw = ld<true>(gptr<hvec>(ch.grad + off));
+        const fvec pv = ld<true>(gptr<fvec>((const float *)ch.master + off));
+        const fvec mv = ld<true>(gptr<fvec>((const float *)ch.exp_avg + off));
+        const fvec vv = ld<true>(gptr<fvec>((const float *)ch.exp_avg_sq + off));
+        float gf[VEC], pp[VEC], mm[VEC], vs[VEC];
+        unpack_lowp<DT, VEC>(graw, gf);
+        split<VEC>(pv, pp);
+        split<VEC>(mv, mm);
+        split<VEC>(vv, vs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) adamw_elem<MODE>(gf[j], pp[j], mm[j], vs[j], k, coef);
+        st<true>(gptr<fvec>(ch.master + off), join<VEC>(pp));
+        st<true>(gptr<fvec>(ch.exp_avg + off), join<VEC>(mm));
+        st<true>(gptr<fvec>(ch.exp_avg_sq + off), join<VEC>(vs));
+        st<true>(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
+    } else {
+        /* ragged end of a chunk: fewer than VEC elements left for this lane */
+        for (uint64_t i = off; i < ch.numel; ++i) {
+            float p = gptr<float>(ch.master)[i], m = gptr<float>(ch.exp_avg)[i], v = gptr<float>(ch.exp_avg_sq)[i];
+            adamw_elem<MODE>(lowp_to_f32<DT>(gptr<uint16_t>(ch.grad)[i]), p, m, v, k, coef);
+            gptr<float>(ch.master)[i] = p;
+            gptr<float>(ch.exp_avg)[i] = m;
+            gptr<float>(ch.exp_avg_sq)[i] = v;
+            gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(p);
+        }
     }
-    (void)n_chunks;
 }
 
 /* ------------------------------------------------------------------------------------- */
@@ -275,8 +307,10 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
     if (threadIdx.x == 0) {
         const double total = s * inv_scale * inv_scale + extra_sumsq;
         const bool bad = !__builtin_isfinite(total);
+        const double nd = bad ? __builtin_nan("") : sqrt(total);
         res->sumsq = total;
-        res->norm = bad ? __builtin_nanf("") : (float)sqrt(total);
+        res->norm_d = nd;
+        res->norm = (float)nd;
         res->found_inf = bad ? 1u : 0u;
         __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); /* re-arm */
     }
@@ -286,8 +320,10 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
 __global__ void set_result_kernel(GradResult *res, double sumsq, uint32_t found_inf)
 {
     const bool bad = found_inf || !__builtin_isfinite(sumsq);
+    const double nd = bad ? __builtin_nan("") : sqrt(sumsq);
     res->sumsq = sumsq;
-    res->norm = bad ? __builtin_nanf("") : (float)sqrt(sumsq);
+    res->norm_d = nd;
+    res->norm = (float)nd;
     res->found_inf = bad ? 1u : 0u;
 }
 
@@ -295,17 +331,18 @@ __global__ void set_result_kernel(GradResult *res, double sumsq, uint32_t found_
 /* Launchers                                                                               */
 /* ------------------------------------------------------------------------------------- */
 
-typedef void (*step_fn)(const DevChunk *, uint32_t, uint64_t, const GradResult *, StepConsts);
+typedef void (*step_fn)(const DevChunk *, const GradResult *, StepConsts);
 
 template <int DT>
 static step_fn pick_step(StepVariant s)
 {
-#define AH_CASE(U, M, N) \
-    if (s.unroll == U && s.mode == M && s.nt == N) return adamw_step_kernel<DT, U, M, (N != 0)>;
-    AH_CASE(1, 0, 0) AH_CASE(2, 0, 0) AH_CASE(4, 0, 0)
-    AH_CASE(1, 1, 0) AH_CASE(2, 1, 0) AH_CASE(4, 1, 0)
-    AH_CASE(1, 0, 1) AH_CASE(2, 0, 1) AH_CASE(4, 0, 1)
-    AH_CASE(1, 1, 1) AH_CASE(2, 1, 1) AH_CASE(4, 1, 1)
+#define AH_CASE(V, B, M) \
+    if (s.vec == V && s.block == B && s.mode == M) return adamw_step_kernel<DT, V, B, M>;
+#define AH_CASES(V, B) AH_CASE(V, B, 0) AH_CASE(V, B, 1)
+    AH_CASES(4, 64) AH_CASES(4, 128) AH_CASES(4, 256)
+    AH_CASES(2, 64) AH_CASES(2, 128) AH_CASES(2, 256)
+    AH_CASES(1, 128) AH_CASES(1, 256) AH_CASES(1, 512)
+#undef AH_CASES
 #undef AH_CASE
     return nullptr;
 }
@@ -315,13 +352,15 @@ static step_fn pick_step(int dtype, StepVariant s)
     return dtype == kFP16 ? pick_step<kFP16>(s) : pick_step<kBF16>(s);
 }
 
-hipError_t launch_step(int dtype, StepVariant var, unsigned blocks, hipStream_t stream, const DevChunk *tab,
-                       uint32_t n_chunks, uint64_t total_tiles, const GradResult *res, const StepConsts &k)
+bool step_variant_valid(StepVariant s) { return pick_step(kBF16, s) != nullptr; }
+
+hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
+                       hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k)
 {
     step_fn fn = pick_step(dtype, var);
     if (!fn) return hipErrorInvalidValue;
-    if (total_tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kThreads), 0, stream, tab, n_chunks, total_tiles, res, k);
+    if (grid_x == 0 || grid_y == 0) return hipSuccess;
+    hipLaunchKernelGGL(fn, dim3(grid_x, grid_y), dim3(var.block), lds_bytes, stream, tab, res, k);
     return hipGetLastError();
 }
 
@@ -343,14 +382,6 @@ hipError_t launch_set_result(hipStream_t stream, GradResult *res, double sumsq, 
 {
     hipLaunchKernelGGL(set_result_kernel, dim3(1), dim3(1), 0, stream, res, sumsq, found_inf);
     return hipGetLastError();
-}
-
-int step_occupancy(int dtype, StepVariant var)
-{
-    step_fn fn = pick_step(dtype, var);
-    int n = 0;
-    if (!fn || hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, kThreads, 0) != hipSuccess) return -1;
-    return n;
 }
 
 int prep_occupancy(int dtype)

@@ -67,11 +67,12 @@ def compare_state(gpu, ora, where=""):
         bad = err > tol
         assert not bad.any(), (where, k, int(bad.sum()), float((err / ulp32(ora[k])).max()))
         stats[k + "_max_ulp"] = float((err / ulp32(ora[k])).max()) if err.size else 0.0
-        stats[k + "_frac_exact"] = float((gpu[k].view(np.uint32) == ora[k].view(np.uint32)).mean()) if err.size else 1.0
+        stats[k + "_mismatch"] = int((gpu[k].view(np.uint32) != ora[k].view(np.uint32)).sum())
     d = np.abs(ordered16(gpu["param_lp"]) - ordered16(ora["param_lp"]))
     assert d.max(initial=0) <= 1, (where, "param_lp", int(d.max()))
     stats["param_lp_max_ulp"] = int(d.max(initial=0))
-    stats["param_lp_frac_exact"] = float((d == 0).mean()) if d.size else 1.0
+    stats["param_lp_mismatch"] = int((d != 0).sum())
+    stats["n"] = int(d.size)
     return stats
 
 

@@ -14,7 +14,8 @@ from paper_2503_01890_amd.modeldata import ModelData, STREAMS
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [u | (m << 4) | (nt << 8) for u in (1, 2, 4) for m in (0, 1) for nt in (0, 1)]
+VARIANTS = [B.step_variant(v, b, m) for v, b in ((4, 64), (4, 128), (4, 256), (2, 64), (2, 128), (2, 256), (1, 128), (1, 256), (1, 512))
+            for m in (0, 1)]
 
 
 def run_gpu(md, ws, dtype, step, hp, extra=0.0, indices=None):
@@ -66,6 +67,7 @@ def test_every_kernel_variant_ragged_multichunk(variant, dtype):
         upload(md, i, st)
     ws = B.Workspace(len(numels))
     ws.tune(B.AH_TUNE_STEP_VARIANT, variant)
+    ws.tune(B.AH_TUNE_STEP_BLOCKS_PER_CU, [0, 3, 64][variant % 3])
     hp = B.hparams(max_grad_norm=0.05)
     for step in (1, 2):
         gn, gf = run_gpu(md, ws, dtype, step, hp, extra=1e-4)
@@ -128,7 +130,7 @@ def test_nonfinite_gradient_skips_bit_exactly(dtype, bad):
         check_norm(gn, gf, on, of)
         assert gf == 0
         for i, st in enumerate(states):
-            compare_state(download(md, i), st)
+            compare_state(download(md, i), st, "after skip")
         ws.close()
 
 
@@ -171,7 +173,7 @@ def test_partition_invariance_and_subsets():
     ora = [{k: v.copy() for k, v in st.items()} for st in states]
     oracle.full_step(ora, oracle.BF16, 5, oracle_hp(hp))
     for a, o in zip(results[0], ora):
-        compare_state(a, o)
+        compare_state(a, o, "partition")
 
 
 def test_result_set_steps_with_host_supplied_norm():
@@ -187,11 +189,11 @@ def test_result_set_steps_with_host_supplied_norm():
     assert ws.autohete_grad_result_get(stream_handle()) == (4.0, 2.0, 0)
     oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], oracle.BF16, 2,
                        oracle_hp(hp), 2.0, 0)
-    compare_state(download(md, 0), st)
+    compare_state(download(md, 0), st, "set")
     ws.autohete_grad_result_set(1.0, 1, stream_handle())            # flagged: step must not touch anything
     ws.autohete_adamw_step(md.chunk_array(), 1, B.AH_BF16, 3, hp, stream_handle())
     torch.cuda.synchronize()
-    compare_state(download(md, 0), st)
+    compare_state(download(md, 0), st, "flagged")
     ws.close()
 
 
@@ -268,6 +270,7 @@ def test_error_codes():
                                   None) == B.AH_EALIGN
     assert lib.autohete_ws_tune(h, 99, 1) == B.AH_EINVAL
     assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_VARIANT, 3) == B.AH_EINVAL
+    assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_BLOCKS_PER_CU, 65) == B.AH_EINVAL
     torch.cuda.synchronize()
     got = download(md, 0)
     assert not got["exp_avg"].any()                                   # rejected calls launched nothing harmful
