@@ -28,6 +28,10 @@ def run_gpu(md, ws, dtype, step, hp, extra=0.0, indices=None):
 
 
 def run_oracle(states, dtype, step, hp, extra=0.0):
+    """Steps the oracle in place; the pre-step master and first moment are kept under "old"."""
+    for st in states:
+        st["old"] = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(),
+                         exp_avg_sq=st["exp_avg_sq"].copy())
     return oracle.full_step(states, dtype, step, oracle_hp(hp), extra)
 
 
@@ -51,7 +55,7 @@ def test_single_chunk_odd_sizes(dtype, n):
         gn, gf = run_gpu(md, ws, dtype, step, hp)
         on, of = run_oracle([st], dtype, step, hp)
         check_norm(gn, gf, on, of)
-        compare_state(download(md, 0), st, "n=%d step=%d" % (n, step))
+        compare_state(download(md, 0), st, "n=%d step=%d" % (n, step), st["old"], drift_steps=step - 1)
     assert np.array_equal(download(md, 0)["grad"], st["grad"])          # gradients are read only
     ws.close()
 
@@ -74,7 +78,8 @@ def test_every_kernel_variant_ragged_multichunk(variant, dtype):
         on, of = run_oracle(states, dtype, step, hp, extra=1e-4)
         check_norm(gn, gf, on, of)
         for i, st in enumerate(states):
-            compare_state(download(md, i), st, "variant=%x chunk=%d" % (variant, i))
+            compare_state(download(md, i), st, "variant=%x chunk=%d" % (variant, i), st["old"],
+                              drift_steps=step - 1)
     ws.close()
 
 
@@ -130,7 +135,7 @@ def test_nonfinite_gradient_skips_bit_exactly(dtype, bad):
         check_norm(gn, gf, on, of)
         assert gf == 0
         for i, st in enumerate(states):
-            compare_state(download(md, i), st, "after skip")
+            compare_state(download(md, i), st, "after skip", st["old"])
         ws.close()
 
 
