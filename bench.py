@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--step-variant", type=lambda x: int(x, 0), default=0, help="AH_TUNE_STEP_VARIANT value (0 = default)")
     ap.add_argument("--blocks-per-cu", type=int, default=0, help="AH_TUNE_STEP_BLOCKS_PER_CU (0 = default)")
     ap.add_argument("--prep-blocks", type=int, default=0, help="AH_TUNE_PREP_BLOCKS (0 = default)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of 4 GiB (known traffic: 4 GiB read + 4 GiB written per "
+                         "launch) so that rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE readings can be scaled")
     ap.add_argument("--cpu-sample-log2", type=int, default=26,
                     help="log2 of the elements per thread in the oracle timing sample")
     return ap.parse_args()
@@ -117,6 +120,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
+        return
     stream = torch.cuda.current_stream().cuda_stream
     w = synthdata.workload(args.workload)
     nres, C = w.n_resident, w.chunk_elems
