@@ -39,38 +39,41 @@ class HParams(ctypes.Structure):
 _lib = None
 
 
+def bind(path):
+    """Load an oracle shared library and declare its prototypes."""
+    L = ctypes.CDLL(path)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    u64p = ctypes.POINTER(ctypes.c_uint64)
+    L.oracle_lowp_decode.restype = ctypes.c_float
+    L.oracle_lowp_decode.argtypes = [ctypes.c_uint16, ctypes.c_int]
+    L.oracle_lowp_encode.restype = ctypes.c_uint16
+    L.oracle_lowp_encode.argtypes = [ctypes.c_float, ctypes.c_int]
+    L.oracle_lowp_decode_array.restype = None
+    L.oracle_lowp_decode_array.argtypes = [u16p, f32p, ctypes.c_uint64, ctypes.c_int]
+    L.oracle_lowp_encode_array.restype = None
+    L.oracle_lowp_encode_array.argtypes = [f32p, u16p, ctypes.c_uint64, ctypes.c_int]
+    L.oracle_chunk_layout.restype = ctypes.c_int
+    L.oracle_chunk_layout.argtypes = [u64p, ctypes.c_uint64, ctypes.c_uint64, u64p, u64p, u64p, u64p]
+    L.oracle_grad_accumulate.restype = None
+    L.oracle_grad_accumulate.argtypes = [u16p, ctypes.c_uint64, ctypes.c_int, ctypes.c_float,
+                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint32)]
+    L.oracle_grad_finish.restype = None
+    L.oracle_grad_finish.argtypes = [ctypes.c_double, ctypes.c_uint32, ctypes.POINTER(ctypes.c_double),
+                                     ctypes.POINTER(ctypes.c_uint32)]
+    L.oracle_clip_coef.restype = ctypes.c_double
+    L.oracle_clip_coef.argtypes = [ctypes.c_double, ctypes.c_float]
+    L.oracle_adamw_chunk.restype = None
+    L.oracle_adamw_chunk.argtypes = [u16p, u16p, f32p, f32p, f32p, ctypes.c_uint64, ctypes.c_int,
+                                     ctypes.c_uint64, ctypes.POINTER(HParams), ctypes.c_double,
+                                     ctypes.c_uint32]
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
-        u16p = ctypes.POINTER(ctypes.c_uint16)
-        f32p = ctypes.POINTER(ctypes.c_float)
-        u64p = ctypes.POINTER(ctypes.c_uint64)
-        L.oracle_lowp_decode.restype = ctypes.c_float
-        L.oracle_lowp_decode.argtypes = [ctypes.c_uint16, ctypes.c_int]
-        L.oracle_lowp_encode.restype = ctypes.c_uint16
-        L.oracle_lowp_encode.argtypes = [ctypes.c_float, ctypes.c_int]
-        L.oracle_lowp_decode_array.restype = None
-        L.oracle_lowp_decode_array.argtypes = [u16p, f32p, ctypes.c_uint64, ctypes.c_int]
-        L.oracle_lowp_encode_array.restype = None
-        L.oracle_lowp_encode_array.argtypes = [f32p, u16p, ctypes.c_uint64, ctypes.c_int]
-        L.oracle_chunk_layout.restype = ctypes.c_int
-        L.oracle_chunk_layout.argtypes = [u64p, ctypes.c_uint64, ctypes.c_uint64, u64p, u64p, u64p, u64p]
-        L.oracle_grad_accumulate.restype = None
-        L.oracle_grad_accumulate.argtypes = [u16p, ctypes.c_uint64, ctypes.c_int, ctypes.c_float,
-                                             ctypes.POINTER(ctypes.c_double),
-                                             ctypes.POINTER(ctypes.c_uint32)]
-        L.oracle_grad_finish.restype = None
-        L.oracle_grad_finish.argtypes = [ctypes.c_double, ctypes.c_uint32,
-                                         ctypes.POINTER(ctypes.c_double),
-                                         ctypes.POINTER(ctypes.c_uint32)]
-        L.oracle_clip_coef.restype = ctypes.c_double
-        L.oracle_clip_coef.argtypes = [ctypes.c_double, ctypes.c_float]
-        L.oracle_adamw_chunk.restype = None
-        L.oracle_adamw_chunk.argtypes = [u16p, u16p, f32p, f32p, f32p, ctypes.c_uint64, ctypes.c_int,
-                                         ctypes.c_uint64, ctypes.POINTER(HParams), ctypes.c_double,
-                                         ctypes.c_uint32]
-        _lib = L
+        _lib = bind(build())
     return _lib
 
 

@@ -8,7 +8,7 @@ namespace ah {
 
 constexpr int kThreads = 256;        /* 4 wavefronts of 64 */
 constexpr int kPrepVec = 8;          /* elements per lane per load in the prep kernel */
-constexpr int kMaxPartials = 16384;  /* upper bound on prep blocks */
+constexpr int kMaxPartials = 16384;  /* upper bound on prep blocks (one fp64 partial each) */
 
 /* Device-side chunk descriptor: the caller's chunk plus the index of its first tile.
  * Entry n_chunks is a sentinel whose tile_begin is the total tile count. */
@@ -56,9 +56,8 @@ hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const Dev
                        uint64_t total_tiles, double inv_scale, double extra_sumsq, double *partials,
                        uint32_t *ticket, GradResult *res);
 hipError_t launch_set_result(hipStream_t stream, GradResult *res, double sumsq, uint32_t found_inf);
-int prep_occupancy(int dtype);   /* resident blocks per CU, <= 0 on error */
 
-constexpr int kPrepUnroll = 2;
+constexpr int kPrepUnroll = 8; /* 8 x 16 B per lane in flight: 32 KB per 256-thread block */
 inline uint32_t prep_tile_elems() { return (uint32_t)(kThreads * kPrepVec * kPrepUnroll); }
 
 }  // namespace ah

@@ -123,6 +123,14 @@ __device__ __forceinline__ void adamw_elem(float gf, float &p, float &m, float &
     p = (float)pn;
 }
 
+/* Clip coefficient min(1, max_norm / (norm + 1e-6)); 1 when clipping is off. */
+__device__ __forceinline__ double clip_coef(double max_norm, double norm)
+{
+    if (!(max_norm > 0.0)) return 1.0;
+    const double c = max_norm / (norm + 1e-6);
+    return c < 1.0 ? c : 1.0;
+}
+
 template <int VEC> struct VecTypes;
 template <> struct VecTypes<4> { typedef f32x4 f32; typedef u32x2 lowp; };
 template <> struct VecTypes<2> { typedef f32x2 f32; typedef uint32_t lowp; };
@@ -188,16 +196,15 @@ template <int DT, int VEC, int BS, int MODE>
 __global__ void __launch_bounds__(BS)
 adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k)
 {
-    /* Skip-on-overflow: leave before the first load; no stream is touched. */
-    if (res->found_inf) return;
+    /* Both scalar fetches (the 32-byte result, the 64-byte table row) are issued together and
+     * feed ONE exit test, so a wave pays two dependent scalar round trips (kernel arguments,
+     * then these) before its vector loads instead of six. */
+    const GradResult r = *res;
     const DevChunk ch = tab[blockIdx.y];
     const uint64_t off = (uint64_t)blockIdx.x * (BS * VEC) + threadIdx.x * VEC;
-    if (off >= ch.numel) return; /* grid.x is the largest tile count of the launch group */
-    double coef = 1.0;
-    if (k.max_norm > 0.0) {
-        const double c = k.max_norm / (res->norm_d + 1e-6);
-        coef = c < 1.0 ? c : 1.0;
-    }
+    /* Skip-on-overflow: leave before the first load, no stream is touched.  Also leave if this
+     * tile lies beyond the chunk (grid.x is the largest tile count of the launch group). */
+    if (r.found_inf | (uint32_t)(off >= ch.numel)) return;
     typedef typename VecTypes<VEC>::f32 fvec;
     typedef typename VecTypes<VEC>::lowp hvec;
     if (off + VEC <= ch.numel) {
@@ -205,6 +212,8 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
         const fvec pv = ld<true>(gptr<fvec>((const float *)ch.master + off));
         const fvec mv = ld<true>(gptr<fvec>((const float *)ch.exp_avg + off));
         const fvec vv = ld<true>(gptr<fvec>((const float *)ch.exp_avg_sq + off));
+        __builtin_amdgcn_sched_barrier(0); /* loads first; the clip factor is computed under them */
+        const double coef = clip_coef(k.max_norm, r.norm_d);
         float gf[VEC], pp[VEC], mm[VEC], vs[VEC];
         unpack_lowp<DT, VEC>(graw, gf);
         split<VEC>(pv, pp);
@@ -218,6 +227,7 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
         st<true>(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
     } else {
         /* ragged end of a chunk: fewer than VEC elements left for this lane */
+        const double coef = clip_coef(k.max_norm, r.norm_d);
         for (uint64_t i = off; i < ch.numel; ++i) {
             float p = gptr<float>(ch.master)[i], m = gptr<float>(ch.exp_avg)[i], v = gptr<float>(ch.exp_avg_sq)[i];
             adamw_elem<MODE>(lowp_to_f32<DT>(gptr<uint16_t>(ch.grad)[i]), p, m, v, k, coef);
@@ -260,17 +270,27 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
      * the end.  fp64 cannot overflow on finite 16-bit inputs, so a non-finite total means a
      * non-finite gradient: the finite check costs no extra instruction per element. */
     double acc0 = 0.0, acc1 = 0.0;
+    /* Chunk cursor: the row of the current chunk is re-read only when the tile index leaves the
+     * chunk (wave-uniform, scalar), so the steady-state iteration issues its vector loads
+     * without waiting on a scalar fetch. */
     uint32_t c = 0;
+    uint64_t c_begin = 0, c_end = 0, numel = 0;
+    const AH_GLOBAL uint16_t *grad = nullptr;
     for (uint64_t w = blockIdx.x; w < total_tiles; w += gridDim.x) {
-        while (w >= tab[c + 1].tile_begin) ++c;
-        const AH_GLOBAL uint16_t *grad = gptr<uint16_t>(tab[c].grad);
-        const uint64_t numel = tab[c].numel;
-        const uint64_t e0 = (w - tab[c].tile_begin) * kTile;
+        if (w >= c_end) {
+            while (w >= tab[c + 1].tile_begin) ++c; /* sentinel row n_chunks ends the search */
+            grad = gptr<uint16_t>(tab[c].grad);
+            numel = tab[c].numel;
+            c_begin = tab[c].tile_begin;
+            c_end = tab[c + 1].tile_begin;
+        }
+        const uint64_t e0 = (w - c_begin) * kTile;
         if (e0 + kTile <= numel) {
             u32x4 g[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 g[u] = ld<true>((const AH_GLOBAL u32x4 *)(grad + e0 + (uint64_t)u * kSub + threadIdx.x * kPrepVec));
+            __builtin_amdgcn_sched_barrier(0); /* all U loads in flight before the first square */
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -382,15 +402,6 @@ hipError_t launch_set_result(hipStream_t stream, GradResult *res, double sumsq, 
 {
     hipLaunchKernelGGL(set_result_kernel, dim3(1), dim3(1), 0, stream, res, sumsq, found_inf);
     return hipGetLastError();
-}
-
-int prep_occupancy(int dtype)
-{
-    int n = 0;
-    hipError_t e = dtype == kFP16
-                       ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, grad_prep_kernel<kFP16>, kThreads, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, grad_prep_kernel<kBF16>, kThreads, 0);
-    return e == hipSuccess ? n : -1;
 }
 
 }  // namespace ah
