@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="gpt-6.7b")
+    ap.add_argument("--path", choices=("fused", "split"), default="fused",
+                    help="fused: prep + adamw_step (headline).  split: prep + adamw_step_master (no 16-bit "
+                         "write-back) + cast_params, the on-demand 16-bit materialisation variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--grad-slabs", type=int, default=0, help="gradient slabs kept resident (0 = one per step if they fit)")
     ap.add_argument("--step-variant", type=lambda x: int(x, 0), default=0, help="AH_TUNE_STEP_VARIANT value (0 = default)")
@@ -163,6 +166,8 @@ def main():
         # host share): what a caller would pass in; here the expected value of the distribution
         extra = float((w.n_valid - n_valid) * (1e-3 ** 2 * (1 - w.outlier_prob) + w.outlier_prob))
 
+    split = args.path == "split"
+
     def one_step(i, t, ev=None):
         arr = arrays[i % n_sets]
         if ev:
@@ -170,14 +175,21 @@ def main():
         ws.autohete_grad_prep(arr, nres, w.dtype, w.loss_scale, extra, stream)
         if ev:
             ev[1].record()
-        ws.autohete_adamw_step(arr, nres, w.dtype, t, hp, stream)
+        if split:
+            ws.autohete_adamw_step_master(arr, nres, w.dtype, t, hp, stream)
+        else:
+            ws.autohete_adamw_step(arr, nres, w.dtype, t, hp, stream)
         if ev:
             ev[2].record()
+        if split:
+            ws.autohete_cast_params(arr, nres, w.dtype, stream)
+            if ev:
+                ev[3].record()
 
     for i in range(args.warmup):
         one_step(i, i + 1)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
         one_step(args.warmup + k, args.warmup + k + 1, events[k])
@@ -189,9 +201,11 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     prep_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     step_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    step_gbps = STEP_BYTES_PER_ELEM * elems / step_ms / 1e6
+    step_bytes = 26 if split else STEP_BYTES_PER_ELEM        # no 16-bit write-back in the split path
+    total_bytes = step_bytes + PREP_BYTES_PER_ELEM + (6 if split else 0)
+    step_gbps = step_bytes * elems / step_ms / 1e6
     prep_gbps = PREP_BYTES_PER_ELEM * elems / prep_ms / 1e6
-    both_gbps = (STEP_BYTES_PER_ELEM + PREP_BYTES_PER_ELEM) * elems / ms_per_step / 1e6
+    both_gbps = total_bytes * elems / ms_per_step / 1e6
 
     out = {
         "metric": "AdamW chunk-update params/sec",
@@ -204,19 +218,24 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.n_valid, "resident_params": n_valid,
                    "chunks": nres, "chunk_elems": C, "lowp": "bf16" if w.dtype == B.AH_BF16 else "fp16",
-                   "grad_slabs_resident": n_sets, "grad_norm": norm,
+                   "path": args.path, "grad_slabs_resident": n_sets, "grad_norm": norm,
                    "hparams": dict(w.hparams, loss_scale=w.loss_scale)},
         "hbm": {"achieved_GBps": both_gbps, "frac_of_peak": both_gbps / HBM_PEAK_GBPS,
-                "bytes_per_param": STEP_BYTES_PER_ELEM + PREP_BYTES_PER_ELEM,
-                "note": "whole step (prep + update), 30 algorithmic bytes per element, wall clock"},
+                "bytes_per_param": total_bytes,
+                "note": "whole step (%s), algorithmic bytes per element, wall clock"
+                        % ("prep + update without 16-bit write-back + cast" if split else "prep + update")},
         "roofline": {"kernel": "adamw_step_kernel", "bound": "hbm", "achieved": step_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": step_gbps / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(w.name),
-                     "algorithmic_bytes_per_launch": STEP_BYTES_PER_ELEM * elems,
+                     "traffic": None if split else measured_traffic(w.name),
+                     "algorithmic_bytes_per_launch": step_bytes * elems,
                      "avg_launch_ms": step_ms},
         "prep_kernel": {"kernel": "grad_prep_kernel", "achieved": prep_gbps, "unit": "GB/s",
                         "frac": prep_gbps / HBM_PEAK_GBPS, "avg_launch_ms": prep_ms},
     }
+    if split:
+        cast_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+        out["cast_kernel"] = {"kernel": "cast_params_kernel", "achieved": 6 * elems / cast_ms / 1e6, "unit": "GB/s",
+                              "frac": 6 * elems / cast_ms / 1e6 / HBM_PEAK_GBPS, "avg_launch_ms": cast_ms}
     ws.close()
     del md
     if not args.no_cpu_baseline:

@@ -137,6 +137,21 @@ int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t 
                         int lowp_dtype, uint64_t step, const autohete_hparams *hp, void *stream);
 
 /*
+ * The same update without the 16-bit write-back: 14 bytes read and 12 bytes written per element;
+ * chunk.param_lp is ignored and may be NULL.  For blocks whose optimizer states stay on the GPU
+ * the paper keeps no 16-bit parameters (section 3.2.2, footnote to the peak-memory model): they
+ * are produced from the fp32 copy just before the block's forward or backward pass and released
+ * afterwards.  autohete_cast_params is that conversion: param_lp = round-to-nearest-even(master),
+ * 4 bytes read and 2 bytes written per element; only .param_lp, .master and .numel are used.
+ * autohete_adamw_step_master followed by autohete_cast_params leaves all five streams
+ * bit-identical to autohete_adamw_step.  Errors as for autohete_adamw_step.
+ */
+int autohete_adamw_step_master(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
+                               int lowp_dtype, uint64_t step, const autohete_hparams *hp, void *stream);
+int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
+                         int lowp_dtype, void *stream);
+
+/*
  * Read (waits for the stream) or overwrite (enqueued on the stream) the workspace's
  * gradient result.  Setting it lets a caller step a block with a norm obtained elsewhere
  * -- e.g. per-block stepping during backward with clipping off (sumsq = 0), or with the

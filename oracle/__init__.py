@@ -67,6 +67,8 @@ def bind(path):
     L.oracle_adamw_chunk.argtypes = [u16p, u16p, f32p, f32p, f32p, ctypes.c_uint64, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.POINTER(HParams), ctypes.c_double,
                                      ctypes.c_uint32]
+    L.oracle_cast_chunk.restype = None
+    L.oracle_cast_chunk.argtypes = [f32p, u16p, ctypes.c_uint64, ctypes.c_int]
     return L
 
 
@@ -149,16 +151,25 @@ def clip_coef(norm, max_grad_norm):
 
 
 def adamw_chunk(grad, param_lp, master, exp_avg, exp_avg_sq, dtype, step, hp, norm, found_inf):
-    """In-place AdamW step on one chunk's arrays."""
+    """In-place AdamW step on one chunk's arrays.  param_lp=None: no 16-bit write-back."""
     n = _chk(grad, np.uint16).size
-    _chk(param_lp, np.uint16), _chk(master, np.float32)
-    _chk(exp_avg, np.float32), _chk(exp_avg_sq, np.float32)
-    if not (param_lp.size == master.size == exp_avg.size == exp_avg_sq.size == n):
+    _chk(master, np.float32), _chk(exp_avg, np.float32), _chk(exp_avg_sq, np.float32)
+    if param_lp is not None:
+        _chk(param_lp, np.uint16)
+    if not ((param_lp is None or param_lp.size == n) and master.size == exp_avg.size == exp_avg_sq.size == n):
         raise ValueError("stream lengths differ")
-    lib().oracle_adamw_chunk(_p(grad, ctypes.c_uint16), _p(param_lp, ctypes.c_uint16),
+    lib().oracle_adamw_chunk(_p(grad, ctypes.c_uint16), None if param_lp is None else _p(param_lp, ctypes.c_uint16),
                              _p(master, ctypes.c_float), _p(exp_avg, ctypes.c_float),
                              _p(exp_avg_sq, ctypes.c_float), n, dtype, int(step),
                              ctypes.byref(hp), float(norm), int(found_inf))
+
+
+def cast_chunk(master, param_lp, dtype):
+    """param_lp = round-to-nearest-even(master), in place."""
+    _chk(master, np.float32), _chk(param_lp, np.uint16)
+    if master.size != param_lp.size:
+        raise ValueError("stream lengths differ")
+    lib().oracle_cast_chunk(_p(master, ctypes.c_float), _p(param_lp, ctypes.c_uint16), master.size, dtype)
 
 
 def full_step(chunks, dtype, step, hp, extra_sumsq=0.0):

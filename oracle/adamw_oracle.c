@@ -210,8 +210,16 @@ void oracle_adamw_chunk(const uint16_t *grad, uint16_t *param_lp, float *master,
         exp_avg[i] = (float)mn;
         exp_avg_sq[i] = (float)vn;
         master[i] = (float)pn;
-        param_lp[i] = oracle_lowp_encode((float)pn, dtype);
+        if (param_lp) param_lp[i] = oracle_lowp_encode((float)pn, dtype);
     }
+}
+
+/* The 16-bit parameters of a chunk produced on demand from the fp32 copy (section 3.2.2,
+ * footnote: blocks whose optimizer states stay on the GPU keep no 16-bit parameters).
+ * oracle_adamw_chunk with param_lp == NULL is the matching update without write-back. */
+void oracle_cast_chunk(const float *master, uint16_t *param_lp, uint64_t numel, int dtype)
+{
+    for (uint64_t i = 0; i < numel; ++i) param_lp[i] = oracle_lowp_encode(master[i], dtype);
 }
 
 /* Vector forms of the 16-bit conversions, for tests. */

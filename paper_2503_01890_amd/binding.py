@@ -59,6 +59,11 @@ _lib.autohete_grad_prep.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chu
 _lib.autohete_adamw_step.restype = ctypes.c_int
 _lib.autohete_adamw_step.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.POINTER(autohete_hparams), ctypes.c_void_p]
+_lib.autohete_adamw_step_master.restype = ctypes.c_int
+_lib.autohete_adamw_step_master.argtypes = _lib.autohete_adamw_step.argtypes
+_lib.autohete_cast_params.restype = ctypes.c_int
+_lib.autohete_cast_params.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int,
+                                      ctypes.c_void_p]
 _lib.autohete_grad_result_get.restype = ctypes.c_int
 _lib.autohete_grad_result_get.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double),
                                           ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint32)]
@@ -127,6 +132,14 @@ class Workspace:
     def autohete_adamw_step(self, chunks, n_chunks, lowp_dtype, step, hp, stream=0):
         _check(_lib.autohete_adamw_step(self._h, chunks, n_chunks, lowp_dtype, int(step), ctypes.byref(hp),
                                         ctypes.c_void_p(stream)), "autohete_adamw_step")
+
+    def autohete_adamw_step_master(self, chunks, n_chunks, lowp_dtype, step, hp, stream=0):
+        _check(_lib.autohete_adamw_step_master(self._h, chunks, n_chunks, lowp_dtype, int(step), ctypes.byref(hp),
+                                               ctypes.c_void_p(stream)), "autohete_adamw_step_master")
+
+    def autohete_cast_params(self, chunks, n_chunks, lowp_dtype, stream=0):
+        _check(_lib.autohete_cast_params(self._h, chunks, n_chunks, lowp_dtype, ctypes.c_void_p(stream)),
+               "autohete_cast_params")
 
     def autohete_grad_result_get(self, stream=0):
         """-> (sumsq, norm, found_inf); waits for the stream."""

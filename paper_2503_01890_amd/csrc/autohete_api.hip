@@ -56,14 +56,17 @@ bool decode_variant(int64_t v, ah::StepVariant *out)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int validate_chunk(const autohete_chunk &c, bool need_all)
+/* Which streams of a chunk a call touches. */
+enum : unsigned { kGrad = 1, kLowp = 2, kMaster = 4, kMom1 = 8, kMom2 = 16 };
+
+int validate_chunk(const autohete_chunk &c, unsigned need)
 {
-    if (c.numel == 0 || !c.grad) return AH_EINVAL;
-    if (need_all && (!c.param_lp || !c.master || !c.exp_avg || !c.exp_avg_sq)) return AH_EINVAL;
-    if (!aligned16(c.grad)) return AH_EALIGN;
-    if (need_all && !(aligned16(c.param_lp) && aligned16(c.master) && aligned16(c.exp_avg) &&
-                      aligned16(c.exp_avg_sq)))
-        return AH_EALIGN;
+    if (c.numel == 0) return AH_EINVAL;
+    const void *ptr[5] = {c.grad, c.param_lp, c.master, c.exp_avg, c.exp_avg_sq};
+    for (int i = 0; i < 5; ++i)
+        if ((need >> i & 1u) && !ptr[i]) return AH_EINVAL;
+    for (int i = 0; i < 5; ++i)
+        if ((need >> i & 1u) && !aligned16(ptr[i])) return AH_EALIGN;
     return AH_OK;
 }
 
@@ -110,7 +113,7 @@ int build_prep_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
     std::vector<DevChunk> tab(n + 1);
     uint64_t tiles = 0;
     for (uint64_t i = 0; i < n; ++i) {
-        int rc = validate_chunk(chunks[i], false);
+        int rc = validate_chunk(chunks[i], kGrad);
         if (rc != AH_OK) return rc;
         fill_row(tab[i], chunks[i], tiles);
         tiles += (chunks[i].numel + tile_elems - 1) / tile_elems;
@@ -126,7 +129,7 @@ int build_prep_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
  * each group can be launched as a 2-D grid (x = tile, y = row) in which at most half of the
  * blocks fall beyond the end of their chunk.  Equal-sized chunks form a single group. */
 int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
-                     hipStream_t stream)
+                     unsigned need, hipStream_t stream)
 {
     if (n > ws->max_chunks) return AH_ENOMEM;
     if (n && !chunks) return AH_EINVAL;
@@ -134,7 +137,7 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
     std::vector<uint32_t> bucket(n);
     uint32_t count[65] = {0};
     for (uint64_t i = 0; i < n; ++i) {
-        int rc = validate_chunk(chunks[i], true);
+        int rc = validate_chunk(chunks[i], need);
         if (rc != AH_OK) return rc;
         tiles[i] = (chunks[i].numel + tile_elems - 1) / tile_elems;
         if (tiles[i] > 0x7FFFFFFFull) return AH_EINVAL; /* grid.x limit: chunk too large */
@@ -334,8 +337,8 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     return AH_OK;
 }
 
-int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
-                        uint64_t step, const autohete_hparams *hp, void *stream_)
+static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                       uint64_t step, const autohete_hparams *hp, void *stream_, bool write_back)
 {
     if (!ws || !hp || step == 0 || (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16)) return AH_EINVAL;
     auto nonneg = [](float x) { return isfinite(x) && x >= 0.0f; };
@@ -348,7 +351,9 @@ int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t 
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     ah::StepVariant var;
     if (!decode_variant(ws->tune_step_variant, &var)) return AH_EINVAL;
-    int rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block), stream);
+    var.write_back = write_back;
+    int rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block),
+                              kGrad | kMaster | kMom1 | kMom2 | (write_back ? kLowp : 0u), stream);
     if (rc != AH_OK) return rc;
     if (n_chunks == 0) return AH_OK;
 
@@ -380,6 +385,35 @@ int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t 
     for (const autohete_ws::Group &grp : ws->step_groups) {
         if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
                             ws->d_tab[1] + grp.first, ws->d_res, k) != hipSuccess)
+            return AH_EHIP;
+    }
+    return AH_OK;
+}
+
+int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                        uint64_t step, const autohete_hparams *hp, void *stream)
+{
+    return step_common(ws, chunks, n_chunks, lowp_dtype, step, hp, stream, true);
+}
+
+int autohete_adamw_step_master(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                               uint64_t step, const autohete_hparams *hp, void *stream)
+{
+    return step_common(ws, chunks, n_chunks, lowp_dtype, step, hp, stream, false);
+}
+
+int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                         void *stream_)
+{
+    if (!ws || (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16)) return AH_EINVAL;
+    DeviceGuard g(ws->device);
+    if (!g.ok) return AH_EHIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, kLowp | kMaster, stream);
+    if (rc != AH_OK) return rc;
+    for (const autohete_ws::Group &grp : ws->step_groups) {
+        if (ah::launch_cast(lowp_dtype, (unsigned)grp.max_tiles, grp.rows, stream, ws->d_tab[1] + grp.first) !=
+            hipSuccess)
             return AH_EHIP;
     }
     return AH_OK;

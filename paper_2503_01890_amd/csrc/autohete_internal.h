@@ -45,13 +45,16 @@ struct StepConsts {
 
 /* Step-kernel variants: vec = elements per lane (1, 2, 4), block = threads per block,
  * mode 0 = fp64 with Newton root/quotient, mode 1 = fp64 with correctly rounded root/quotient. */
-struct StepVariant { int vec, block, mode; };
+struct StepVariant { int vec, block, mode; bool write_back = true; };
 bool step_variant_valid(StepVariant s);
 
 /* grid_x tiles of vec*block elements for each of grid_y table rows; lds_bytes of dynamic LDS
  * per block caps the blocks resident per CU. */
 hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
                        hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k);
+/* master -> 16-bit conversion: grid_x tiles of 512 elements for each of grid_y table rows */
+constexpr uint32_t kCastTileElems = 512;
+hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, hipStream_t stream, const DevChunk *tab);
 hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const DevChunk *tab, uint32_t n_chunks,
                        uint64_t total_tiles, double inv_scale, double extra_sumsq, double *partials,
                        uint32_t *ticket, GradResult *res);

@@ -191,8 +191,11 @@ __device__ __forceinline__ typename VecTypes<VEC>::f32 join(const float *in)
  * the launcher (through the dynamic LDS size): about 30 KB of loads in flight per CU is the
  * measured optimum, more in flight widens the window and costs bandwidth.
  * All accesses are non-temporal: every byte is touched exactly once per step.
+ * WB = false leaves out the 16-bit write-back (26 B/element): the variant for blocks whose
+ * 16-bit parameters are only materialised on demand (cast_params_kernel; paper section 3.2.2,
+ * footnote on GPU-resident optimizer states).
  */
-template <int DT, int VEC, int BS, int MODE>
+template <int DT, int VEC, int BS, int MODE, bool WB>
 __global__ void __launch_bounds__(BS)
 adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k)
 {
@@ -224,7 +227,7 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
         st<true>(gptr<fvec>(ch.master + off), join<VEC>(pp));
         st<true>(gptr<fvec>(ch.exp_avg + off), join<VEC>(mm));
         st<true>(gptr<fvec>(ch.exp_avg_sq + off), join<VEC>(vs));
-        st<true>(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
+        if constexpr (WB) st<true>(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
     } else {
         /* ragged end of a chunk: fewer than VEC elements left for this lane */
         const double coef = clip_coef(k.max_norm, r.norm_d);
@@ -234,7 +237,35 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
             gptr<float>(ch.master)[i] = p;
             gptr<float>(ch.exp_avg)[i] = m;
             gptr<float>(ch.exp_avg_sq)[i] = v;
-            gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(p);
+            if constexpr (WB) gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(p);
+        }
+    }
+}
+
+/*
+ * On-demand materialisation of the 16-bit parameters from the fp32 master copy (paper section
+ * 3.2.2, footnote: blocks whose optimizer states stay on the GPU keep no 16-bit parameters; they
+ * are converted from the fp32 ones just before the block's forward / backward pass and released
+ * afterwards).  4 B read + 2 B written per element, round-to-nearest-even.  One wavefront per
+ * 512-element tile: lane l converts elements [4l, 4l+4) and [256+4l, 256+4l+4), so both loads
+ * and both stores of a wave are contiguous.
+ */
+template <int DT>
+__global__ void __launch_bounds__(64) cast_params_kernel(const DevChunk *__restrict__ tab)
+{
+    const DevChunk ch = tab[blockIdx.y];
+    const uint64_t base = (uint64_t)blockIdx.x * 512 + threadIdx.x * 4;
+    if (base >= ch.numel) return;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint64_t off = base + (uint64_t)h * 256;
+        if (off + 4 <= ch.numel) {
+            const f32x4 pv = ld<true>(gptr<f32x4>((const float *)ch.master + off));
+            float pp[4] = {pv[0], pv[1], pv[2], pv[3]};
+            st<true>(gptr<u32x2>(ch.param_lp + off), pack_lowp<DT, 4>(pp));
+        } else {
+            for (uint64_t i = off; i < ch.numel; ++i)
+                gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(gptr<float>(ch.master)[i]);
         }
     }
 }
@@ -357,7 +388,8 @@ template <int DT>
 static step_fn pick_step(StepVariant s)
 {
 #define AH_CASE(V, B, M) \
-    if (s.vec == V && s.block == B && s.mode == M) return adamw_step_kernel<DT, V, B, M>;
+    if (s.vec == V && s.block == B && s.mode == M) \
+        return s.write_back ? adamw_step_kernel<DT, V, B, M, true> : adamw_step_kernel<DT, V, B, M, false>;
 #define AH_CASES(V, B) AH_CASE(V, B, 0) AH_CASE(V, B, 1)
     AH_CASES(4, 64) AH_CASES(4, 128) AH_CASES(4, 256)
     AH_CASES(2, 64) AH_CASES(2, 128) AH_CASES(2, 256)
@@ -373,6 +405,16 @@ static step_fn pick_step(int dtype, StepVariant s)
 }
 
 bool step_variant_valid(StepVariant s) { return pick_step(kBF16, s) != nullptr; }
+
+hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, hipStream_t stream, const DevChunk *tab)
+{
+    if (grid_x == 0 || grid_y == 0) return hipSuccess;
+    if (dtype == kFP16)
+        hipLaunchKernelGGL(cast_params_kernel<kFP16>, dim3(grid_x, grid_y), dim3(64), 0, stream, tab);
+    else
+        hipLaunchKernelGGL(cast_params_kernel<kBF16>, dim3(grid_x, grid_y), dim3(64), 0, stream, tab);
+    return hipGetLastError();
+}
 
 hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
                        hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k)

@@ -319,3 +319,53 @@ def test_padding_stays_zero_and_checkpoint_resume():
     resumed = download(md3, 0)
     assert all(straight[s].tobytes() == resumed[s].tobytes() for s in STREAMS)
     ws.close(), ws3.close()
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+def test_split_path_master_only_step_then_cast(dtype):
+    """autohete_adamw_step_master leaves the 16-bit parameters alone (and accepts NULL for them);
+    followed by autohete_cast_params it is bit-identical to the fused step; both match the oracle."""
+    rng = np.random.default_rng(77 + dtype)
+    numels = [1, 3, 255, 256, 257, 511, 512, 513, 4099, 20_000, 65536 + 5]
+    states = [random_state(n, dtype, rng) for n in numels]
+    hp = B.hparams(max_grad_norm=0.02)
+    fused, split = ModelData(numels), ModelData(numels)
+    for i, st in enumerate(states):
+        upload(fused, i, st)
+        upload(split, i, st)
+    ws = B.Workspace(len(numels))
+    n = len(numels)
+    for step in (1, 2):
+        run_gpu(fused, ws, dtype, step, hp)
+        arr = split.chunk_array()
+        ws.autohete_grad_prep(arr, n, dtype, 1.0, 0.0, stream_handle())
+        no_lp = B.chunk_array([(t[0], None) + t[2:] for t in (split.chunk_tuple(i) for i in range(n))])
+        before = [download(split, i, ("param_lp",))["param_lp"] for i in range(n)]
+        ws.autohete_adamw_step_master(no_lp, n, dtype, step, hp, stream_handle())
+        torch.cuda.synchronize()
+        for i in range(n):
+            assert np.array_equal(download(split, i, ("param_lp",))["param_lp"], before[i])
+        ws.autohete_cast_params(arr, n, dtype, stream_handle())
+        torch.cuda.synchronize()
+        run_oracle(states, dtype, step, hp)
+        for i, st in enumerate(states):
+            a, b = download(fused, i), download(split, i)
+            assert all(a[s].tobytes() == b[s].tobytes() for s in STREAMS), (step, i)
+            compare_state(b, st, "split step=%d chunk=%d" % (step, i), st["old"], drift_steps=step - 1)
+    # cast alone: any fp32 values, incl. ties, overflow to inf (fp16), subnormals, zeros, NaN stays NaN
+    vals = np.concatenate([rng.normal(0, 1, 5000), [0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e-8, 6e-8, -3e-8, 3.4e38],
+                           np.float32(1.0) + np.arange(0, 64) * np.float32(2.0 ** -12)]).astype(np.float32)
+    md = ModelData([vals.size])
+    md.view("master", 0).copy_(torch.from_numpy(vals))
+    ws.autohete_cast_params(md.chunk_array(), 1, dtype, stream_handle())
+    torch.cuda.synchronize()
+    got = download(md, 0, ("param_lp",))["param_lp"]
+    assert np.array_equal(got, oracle.encode(vals, dtype))
+    lib, s = B.raw(), ctypes.c_void_p(stream_handle())
+    t = list(md.chunk_tuple(0))
+    t[2] = None
+    assert lib.autohete_cast_params(ws._h, B.chunk_array([t]), 1, dtype, s) == B.AH_EINVAL
+    t = list(md.chunk_tuple(0))
+    t[1] += 2
+    assert lib.autohete_cast_params(ws._h, B.chunk_array([t]), 1, dtype, s) == B.AH_EALIGN
+    ws.close()

@@ -34,7 +34,13 @@ class Run:
     """Device state + oracle-side sampled state of one workload across its iterations."""
 
     def __init__(self, name):
+        # "<workload>+split": the same workload stepped through autohete_adamw_step_master followed by
+        # autohete_cast_params (16-bit parameters materialised on demand), fewer iterations
+        self.split = name.endswith("+split")
+        name = name.split("+")[0]
         self.w = w = synthdata.workload(name)
+        if self.split:
+            w.steps = 3
         self.C = w.chunk_elems
         self.md = ModelData([self.C] * w.n_resident)
         for c in range(w.n_resident):
@@ -92,7 +98,11 @@ class Run:
         before = self.checksums() if it in w.inject else None
         gn, gf = self.ws.autohete_grad_prep(self.arr, w.n_resident, w.dtype, scale, extra, stream_handle(),
                                             want_result=True)
-        self.ws.autohete_adamw_step(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
+        if self.split:
+            self.ws.autohete_adamw_step_master(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
+            self.ws.autohete_cast_params(self.arr, w.n_resident, w.dtype, stream_handle())
+        else:
+            self.ws.autohete_adamw_step(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
         torch.cuda.synchronize()
         # oracle: norm over every resident chunk, then the sampled chunks element by element
         s, f = oracle_sumsq_over_chunks(w, range(w.n_resident), it, scale, patch)
@@ -110,8 +120,14 @@ class Run:
                     g[pi] = bits
             h = self.host[c]
             old = dict(master=h["master"].copy(), exp_avg=h["exp_avg"].copy(), exp_avg_sq=h["exp_avg_sq"].copy())
-            oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
-                               oracle_hp(hp), on, of)
+            if self.split:
+                oracle.adamw_chunk(g, None, h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
+                                   oracle_hp(hp), on, of)
+                if not of:
+                    oracle.cast_chunk(h["master"], h["param_lp"], w.dtype)
+            else:
+                oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
+                                   oracle_hp(hp), on, of)
             got = download(md, c, ("param_lp", "master", "exp_avg", "exp_avg_sq"))
             st = compare_state(got, h, "%s it=%d chunk=%d" % (w.name, it, c), old,
                                drift_steps=(self.t - 1 if c == self.free else 0))
@@ -140,7 +156,7 @@ class Run:
                                                             "exp_avg_sq_mismatch", "param_lp_mismatch",
                                                             "master_relaxed", "exp_avg_relaxed", "exp_avg_sq_relaxed")}
         os.makedirs("gpurun_out", exist_ok=True)
-        with open("gpurun_out/parity_%s.txt" % w.name, "w") as fh:
+        with open("gpurun_out/parity_%s%s.txt" % (w.name, "_split" if self.split else ""), "w") as fh:
             fh.write("workload %s: %d iterations, %d updates, sampled chunks %s (free-running: %s)\n" %
                      (w.name, self.done, self.t - 1, self.sample, self.free))
             fh.write("element-steps compared: %d\nworst error vs oracle (ulp, cancelled elements aside): %s\n"
@@ -163,8 +179,10 @@ def get_run(name):
 
 
 def cases():
-    for name in synthdata.WORKLOADS:
-        w = synthdata.workload(name)
+    for name in synthdata.WORKLOADS + ("gpt-1.3b+split",):
+        w = synthdata.workload(name.split("+")[0])
+        if "+" in name:
+            w.steps = 3
         for it in range(1, w.steps + 1):
             yield pytest.param(name, it, id="%s-it%d" % (name, it))
         yield pytest.param(name, 0, id="%s-finish" % name)

@@ -43,12 +43,14 @@ MUTATIONS = {
     "fp16_bias_wrong": ("else mag = ldexp(1024.0 + f, e - 15 - 10);", "else mag = ldexp(1024.0 + f, e - 16 - 10);"),
     "fp16_subnormals_flushed": ("if (e < emin) e = emin;", "if (e < emin) return (uint16_t)(sign << 15);"),
     "bf16_mantissa_width": ("return encode_grid((double)x, 7, -126, 127, 127);", "return encode_grid((double)x, 8, -126, 127, 127);"),
+    "cast_truncates": ("param_lp[i] = oracle_lowp_encode(master[i], dtype);", "param_lp[i] = (uint16_t)(oracle_lowp_encode(master[i], dtype) & 0xFFFEu);"),
+    "no_writeback_variant_still_skips_master": ("        if (param_lp) param_lp[i] = oracle_lowp_encode((float)pn, dtype);", "        if (param_lp) param_lp[i] = oracle_lowp_encode((float)pn, dtype); else master[i] = (float)p;"),
     "layout_one_chunk_too_many": ("while (nc * chunk_elems < off) ++nc;", "while (nc * chunk_elems <= off) ++nc;"),
     "layout_offsets_inclusive": ("        tensor_offset[t] = off;\n        off += tensor_numel[t];", "        off += tensor_numel[t];\n        tensor_offset[t] = off;"),
 }
 
 # cheap pins first; each mutation stops at the first pin that fails
-BATTERY = [pins.test_hand_worked_examples, pins.test_zero_gradient_is_pure_decay, pins.test_step1_is_lr_sign_g,
+BATTERY = [pins.test_hand_worked_examples, pins.test_split_path_equals_fused_and_cast_is_library_rne, pins.test_zero_gradient_is_pure_decay, pins.test_step1_is_lr_sign_g,
            pins.test_norm_closed_forms, pins.test_nonfinite_extra_sumsq_sets_flag, pins.test_clip_invariants,
            pins.test_chunk_layout_against_cumsum_and_counts, pins.test_decode_all_patterns_match_numpy_and_torch,
            pins.test_encode_roundtrip_all_patterns, pins.test_constant_gradient_closed_form_every_t,

@@ -373,3 +373,27 @@ def test_padding_stays_zero():
         oracle.full_step([dict(grad=live, **state(n, BF16)), z], BF16, t, oracle.hparams())
         for k in z:
             assert not z[k].view(np.uint8).any(), k          # +0 bit pattern, not -0
+
+
+def test_split_path_equals_fused_and_cast_is_library_rne():
+    """Update without 16-bit write-back + on-demand cast == fused update, bit for bit; the cast is
+    the format conversion (checked against torch / numpy, which the oracle does not call)."""
+    n = 5000
+    for dtype in (BF16, FP16):
+        g = lowp(RNG.normal(0, 1e-3, n), dtype)
+        fused = state(n, dtype, rng=np.random.default_rng(3))
+        split = {k: v.copy() for k, v in fused.items()}
+        hp = oracle.hparams()
+        norm, flag = oracle.grad_prep([g], dtype, 1.0)
+        oracle.adamw_chunk(g, fused["param_lp"], fused["master"], fused["exp_avg"], fused["exp_avg_sq"], dtype, 2, hp,
+                           norm, flag)
+        stale = split["param_lp"].copy()
+        oracle.adamw_chunk(g, None, split["master"], split["exp_avg"], split["exp_avg_sq"], dtype, 2, hp, norm, flag)
+        assert np.array_equal(split["param_lp"], stale)                   # untouched without write-back
+        oracle.cast_chunk(split["master"], split["param_lp"], dtype)
+        assert all(fused[k].tobytes() == split[k].tobytes() for k in fused)
+        if dtype == BF16:
+            ref = torch.tensor(split["master"]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        else:
+            ref = split["master"].astype(np.float16).view(np.uint16)
+        assert np.array_equal(split["param_lp"], ref)
