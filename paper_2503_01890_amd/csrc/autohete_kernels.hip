@@ -55,6 +55,25 @@ __device__ __forceinline__ void st(AH_GLOBAL T *p, T v)
     else *p = v;
 }
 
+/* Streaming store of the update kernels: non-temporal AND system-scope write-through
+ * ("sc1 nt").  Measured against every combination of the sc0/sc1/nt bits on this access
+ * pattern, stores with sc1+nt are ~1 % faster than nt alone (and nt alone ~13 % faster than
+ * plain stores when the loads are nt); the load policy makes no difference beyond nt.  The
+ * compiler has no builtin for this combination on vector types, hence the inline assembly; the
+ * stored lines are never read again by this kernel, so no wait is needed after them.  The
+ * trailing s_nop supplies, by hand, the one wait state the ISA requires between a VMEM store of
+ * more than 64 bits and a VALU write to its data registers: the compiler inserts it for its own
+ * stores but cannot see into an asm statement. */
+template <typename T>
+__device__ __forceinline__ void st_stream(AH_GLOBAL T *p, T v)
+{
+    static_assert(sizeof(T) == 16 || sizeof(T) == 8 || sizeof(T) == 4 || sizeof(T) == 2, "store width");
+    if constexpr (sizeof(T) == 16) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
+    else if constexpr (sizeof(T) == 8) asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
+    else if constexpr (sizeof(T) == 4) asm volatile("global_store_dword %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
+    else asm volatile("global_store_short %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"((uint32_t)v) : "memory");
+}
+
 /* 16-bit <-> fp32.  bf16 is the upper half of an fp32 word; fp16 uses the hardware converts.
  * Both encodes round to nearest even and keep subnormals. */
 template <int DT>
@@ -224,10 +243,10 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
         split<VEC>(vv, vs);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) adamw_elem<MODE>(gf[j], pp[j], mm[j], vs[j], k, coef);
-        st<true>(gptr<fvec>(ch.master + off), join<VEC>(pp));
-        st<true>(gptr<fvec>(ch.exp_avg + off), join<VEC>(mm));
-        st<true>(gptr<fvec>(ch.exp_avg_sq + off), join<VEC>(vs));
-        if constexpr (WB) st<true>(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
+        st_stream(gptr<fvec>(ch.master + off), join<VEC>(pp));
+        st_stream(gptr<fvec>(ch.exp_avg + off), join<VEC>(mm));
+        st_stream(gptr<fvec>(ch.exp_avg_sq + off), join<VEC>(vs));
+        if constexpr (WB) st_stream(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
     } else {
         /* ragged end of a chunk: fewer than VEC elements left for this lane */
         const double coef = clip_coef(k.max_norm, r.norm_d);
@@ -262,7 +281,7 @@ __global__ void __launch_bounds__(64) cast_params_kernel(const DevChunk *__restr
         if (off + 4 <= ch.numel) {
             const f32x4 pv = ld<true>(gptr<f32x4>((const float *)ch.master + off));
             float pp[4] = {pv[0], pv[1], pv[2], pv[3]};
-            st<true>(gptr<u32x2>(ch.param_lp + off), pack_lowp<DT, 4>(pp));
+            st_stream(gptr<u32x2>(ch.param_lp + off), pack_lowp<DT, 4>(pp));
         } else {
             for (uint64_t i = off; i < ch.numel; ++i)
                 gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(gptr<float>(ch.master)[i]);
