@@ -19,6 +19,15 @@ def step_variant(vec=4, block=64, mode=0):
     """Encode a value for AH_TUNE_STEP_VARIANT."""
     return vec | (mode << 4) | ((block // 64) << 8)
 
+# PyTorch-ROCm ships its own copy of the HIP runtime (same SONAME as the system one).  The device
+# pointers and streams this binding is handed belong to THAT runtime instance, so it must already
+# be in the process when libautohete.so resolves its libamdhip64 dependency; loaded the other way
+# round, the process ends up with two HIP runtimes that do not share allocations or streams.
+try:
+    import torch  # noqa: F401
+except ImportError:  # a caller that manages device memory through the system HIP runtime
+    pass
+
 if not os.path.exists(LIB_PATH):
     raise ImportError("libautohete.so is not built (%s): run __graft_entry__.build() or "
                       "python paper_2503_01890_amd/build.py" % LIB_PATH)

@@ -69,6 +69,10 @@ def _gpu_lib():
     if _gpu is None:
         if not os.path.exists(_GPU_LIB):
             raise RuntimeError("libsynth_gpu.so is not built: run __graft_entry__.build() first")
+        try:
+            import torch  # noqa: F401  (its bundled HIP runtime must be the one this library binds to)
+        except ImportError:
+            pass
         _gpu = ctypes.CDLL(_GPU_LIB)
         _gpu.synth_gpu_fill.restype = ctypes.c_int
         _gpu.synth_gpu_fill.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.POINTER(Spec), ctypes.c_void_p]

@@ -25,7 +25,7 @@
 #include <stdint.h>
 
 #ifndef SYNTH_HD
-#define SYNTH_HD static inline
+#define SYNTH_HD static inline __attribute__((always_inline))
 #endif
 
 #define SYNTH_GOLD 0x9E3779B97F4A7C15ull
@@ -94,21 +94,19 @@ SYNTH_HD float synth_from_fp16(uint16_t h)
     return synth_bits_f32(sign | ((e + 112u) << 23) | (f << 13));
 }
 
+/* Branch-free on purpose (selects only), so that the CPU fill loops vectorise. */
 SYNTH_HD float synth_value(const synth_spec *s, uint64_t idx)
 {
-    if (idx >= s->n_valid) return 0.0f;
     uint64_t h1 = synth_mix64(s->key + SYNTH_GOLD * idx);
     uint64_t h2 = synth_mix64(h1 + SYNTH_GOLD2);
+    uint64_t h3 = synth_mix64(h2 + SYNTH_GOLD);
     int32_t z = (int32_t)((h1 & 0xFFFF) + ((h1 >> 16) & 0xFFFF) + ((h1 >> 32) & 0xFFFF) + (h1 >> 48) +
                           (h2 & 0xFFFF) + ((h2 >> 16) & 0xFFFF) + ((h2 >> 32) & 0xFFFF) + (h2 >> 48)) - 262140;
-    float sc = s->scale;
-    if (s->outlier_thresh) {
-        uint64_t h3 = synth_mix64(h2 + SYNTH_GOLD);
-        if ((uint32_t)(h3 >> 32) < s->outlier_thresh) sc = s->scale_outlier;
-    }
+    int outlier = (uint32_t)(h3 >> 32) < s->outlier_thresh; /* thresh 0: never */
+    float sc = outlier ? s->scale_outlier : s->scale;
     float x = (float)z * sc;
-    if (s->take_abs && z < 0) x = -x;
-    return x;
+    float ax = (s->take_abs && z < 0) ? -x : x;
+    return idx >= s->n_valid ? 0.0f : ax;
 }
 
 /* Writes element idx of the stream at out[idx - first_index]. */

@@ -10,6 +10,7 @@ of the seeded generator; the oracle regenerates what it needs on the CPU from th
     one sampled chunk is left free-running and judged with the drift allowance instead.
 Whole-slab bit-exactness on skipped iterations is checked with device-side checksums.
 Each iteration is its own test so that no single test runs for minutes."""
+import concurrent.futures as cf
 import os
 
 import numpy as np
@@ -18,7 +19,7 @@ import torch
 
 import oracle
 import synthdata
-from _harness import (compare_state, cpu_chunk_grad, cpu_chunk_state, download, fill_device_chunk,
+from _harness import (N_THREADS, compare_state, cpu_chunk_grad, cpu_chunk_state, download, fill_device_chunk,
                       oracle_hp, oracle_sumsq_over_chunks, stream_handle, upload)
 from paper_2503_01890_amd import binding as B
 from paper_2503_01890_amd.modeldata import ModelData, STREAMS
@@ -113,7 +114,7 @@ class Run:
             assert self.checksums() == before, "a skipped step must leave every stream bit-identical"
         else:
             assert abs(gn - on) <= 1e-5 * on, (it, gn, on)
-        for c in self.sample:
+        def oracle_step(c):          # runs in a worker thread; the C calls release the GIL
             g = cpu_chunk_grad(w, c, it, scale)
             for (pc, pi), bits in patch.items():
                 if pc == c:
@@ -128,6 +129,12 @@ class Run:
             else:
                 oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
                                    oracle_hp(hp), on, of)
+            return old
+
+        with cf.ThreadPoolExecutor(min(N_THREADS, len(self.sample))) as ex:
+            olds = dict(zip(self.sample, ex.map(oracle_step, self.sample)))
+        for c in self.sample:
+            h, old = self.host[c], olds.pop(c)
             got = download(md, c, ("param_lp", "master", "exp_avg", "exp_avg_sq"))
             st = compare_state(got, h, "%s it=%d chunk=%d" % (w.name, it, c), old,
                                drift_steps=(self.t - 1 if c == self.free else 0))
