@@ -233,11 +233,14 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
     if (!ws) return AH_ENOMEM;
     ws->max_chunks = max_chunks;
     hipDeviceProp_t prop;
-    bool ok = hipGetDevice(&ws->device) == hipSuccess && hipGetDeviceProperties(&prop, ws->device) == hipSuccess;
-    if (ok) {
-        ws->n_cu = prop.multiProcessorCount;
-        ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+    if (hipGetDevice(&ws->device) != hipSuccess || hipGetDeviceProperties(&prop, ws->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete ws;
+        return AH_EHIP;
     }
+    ws->n_cu = prop.multiProcessorCount;
+    ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+    bool ok = true;
     const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
     for (int s = 0; ok && s < 2; ++s) {
         ok = hipMalloc(&ws->d_tab[s], tab_bytes) == hipSuccess &&
@@ -247,14 +250,18 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
     ok = ok && hipMalloc(&ws->d_partials, ah::kMaxPartials * sizeof(double)) == hipSuccess &&
          hipMalloc(&ws->d_ticket, 256) == hipSuccess && hipMalloc(&ws->d_res, 256) == hipSuccess &&
          hipHostMalloc(&ws->h_res, sizeof(GradResult), hipHostMallocDefault) == hipSuccess;
-    /* The ticket must start at zero (each prep launch re-arms it); the result starts as
-     * "no gradient seen": S = 0, no skip. */
-    ok = ok && hipMemset(ws->d_ticket, 0, 256) == hipSuccess && hipMemset(ws->d_res, 0, 256) == hipSuccess &&
-         hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         autohete_ws_destroy(ws);
         return AH_ENOMEM;
+    }
+    /* The ticket must start at zero (each prep launch re-arms it); the result starts as
+     * "no gradient seen": S = 0, no skip. */
+    if (hipMemset(ws->d_ticket, 0, 256) != hipSuccess || hipMemset(ws->d_res, 0, 256) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        autohete_ws_destroy(ws);
+        return AH_EHIP;
     }
     *out = ws;
     return AH_OK;
@@ -321,7 +328,12 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     if (!g.ok) return AH_EHIP;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     uint64_t tiles = 0;
-    int rc = build_prep_table(ws, chunks, n_chunks, ah::prep_tile_elems(), stream, &tiles);
+    int rc;
+    try {
+        rc = build_prep_table(ws, chunks, n_chunks, ah::prep_tile_elems(), stream, &tiles);
+    } catch (...) { /* std::bad_alloc from the host-side table: nothing may be thrown across the C ABI */
+        return AH_ENOMEM;
+    }
     if (rc != AH_OK) return rc;
 
     /* One 256-thread block per CU, each with 32 KB of loads in flight: the measured optimum for
@@ -352,8 +364,13 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     ah::StepVariant var;
     if (!decode_variant(ws->tune_step_variant, &var)) return AH_EINVAL;
     var.write_back = write_back;
-    int rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block),
+    int rc;
+    try {
+        rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block),
                               kGrad | kMaster | kMom1 | kMom2 | (write_back ? kLowp : 0u), stream);
+    } catch (...) {
+        return AH_ENOMEM;
+    }
     if (rc != AH_OK) return rc;
     if (n_chunks == 0) return AH_OK;
 
@@ -409,7 +426,12 @@ int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t
     DeviceGuard g(ws->device);
     if (!g.ok) return AH_EHIP;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    int rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, kLowp | kMaster, stream);
+    int rc;
+    try {
+        rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, kLowp | kMaster, stream);
+    } catch (...) {
+        return AH_ENOMEM;
+    }
     if (rc != AH_OK) return rc;
     for (const autohete_ws::Group &grp : ws->step_groups) {
         if (ah::launch_cast(lowp_dtype, (unsigned)grp.max_tiles, grp.rows, stream, ws->d_tab[1] + grp.first) !=
