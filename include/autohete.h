@@ -119,6 +119,18 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
                        float *norm_out, uint32_t *found_inf_out);
 
 /*
+ * The same pass, folded into the result already in the workspace instead of replacing it:
+ * S += sum (grad / loss_scale)^2 over the given chunks, skip flag |= non-finite.  Lets a caller
+ * gather the global norm block by block as the backward pass produces gradients (the paper steps
+ * each block's optimizer as soon as its gradients exist: section 3.2.2, footnote to Eq. 5), starting
+ * from autohete_grad_result_set(ws, 0, 0, stream).  Chunks may be sub-ranges of larger chunks (any
+ * 16-byte-aligned slice).  The result equals one autohete_grad_prep over all the chunks up to the
+ * order of the fp64 additions.
+ */
+int autohete_grad_prep_accumulate(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
+                                  int lowp_dtype, float loss_scale, void *stream);
+
+/*
  * The update (rule at the top of this file) over the given chunks in one fused pass:
  * 14 bytes read and 14 bytes written per element; each optimizer state is read once and
  * written once per update (the paper's appendix on memory allocation states the same).  It consumes the workspace's

@@ -65,6 +65,9 @@ _lib.autohete_grad_prep.restype = ctypes.c_int
 _lib.autohete_grad_prep.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int,
                                     ctypes.c_float, ctypes.c_double, ctypes.c_void_p,
                                     ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint32)]
+_lib.autohete_grad_prep_accumulate.restype = ctypes.c_int
+_lib.autohete_grad_prep_accumulate.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64,
+                                               ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
 _lib.autohete_adamw_step.restype = ctypes.c_int
 _lib.autohete_adamw_step.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.POINTER(autohete_hparams), ctypes.c_void_p]
@@ -137,6 +140,10 @@ class Workspace:
         _check(_lib.autohete_grad_prep(self._h, chunks, n_chunks, lowp_dtype, loss_scale, extra_sumsq,
                                        ctypes.c_void_p(stream), None, None), "autohete_grad_prep")
         return None
+
+    def autohete_grad_prep_accumulate(self, chunks, n_chunks, lowp_dtype, loss_scale, stream=0):
+        _check(_lib.autohete_grad_prep_accumulate(self._h, chunks, n_chunks, lowp_dtype, loss_scale,
+                                                  ctypes.c_void_p(stream)), "autohete_grad_prep_accumulate")
 
     def autohete_adamw_step(self, chunks, n_chunks, lowp_dtype, step, hp, stream=0):
         _check(_lib.autohete_adamw_step(self._h, chunks, n_chunks, lowp_dtype, int(step), ctypes.byref(hp),

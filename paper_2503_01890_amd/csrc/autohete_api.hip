@@ -23,10 +23,16 @@ struct autohete_ws {
     uint64_t max_chunks = 0;
     /* slot 0: table of the last grad_prep call, slot 1: of the last adamw_step call */
     DevChunk *d_tab[2] = {nullptr, nullptr};
-    DevChunk *h_stage[2] = {nullptr, nullptr}; /* pinned staging for the async upload */
+    /* Pinned staging for the asynchronous table uploads: a small ring per slot, so that a caller
+     * that changes its chunk list on every call (per-block stepping) does not have to wait for
+     * the previous upload -- queued behind earlier kernels -- before it can stage the next one. */
+    static constexpr int kRing = 8;
+    int ring_depth = 1;
+    int ring_next[2] = {0, 0};
+    DevChunk *h_stage[2][kRing] = {};
+    hipEvent_t staged[2][kRing] = {};           /* upload from h_stage[slot][i] has completed */
+    bool staged_pending[2][kRing] = {};
     std::vector<DevChunk> h_last[2];            /* what d_tab holds */
-    hipEvent_t staged[2] = {nullptr, nullptr};  /* upload from h_stage has completed */
-    bool staged_pending[2] = {false, false};
     double *d_partials = nullptr;
     uint32_t *d_ticket = nullptr;
     GradResult *d_res = nullptr;
@@ -89,16 +95,18 @@ int upload_table(autohete_ws *ws, int slot, std::vector<DevChunk> &tab, hipStrea
     *changed = !(last.size() == tab.size() &&
                  memcmp(last.data(), tab.data(), tab.size() * sizeof(DevChunk)) == 0);
     if (!*changed) return AH_OK;
-    if (ws->staged_pending[slot]) { /* the previous upload may still be reading the staging buffer */
-        if (hipEventSynchronize(ws->staged[slot]) != hipSuccess) return AH_EHIP;
-        ws->staged_pending[slot] = false;
+    const int r = ws->ring_next[slot];
+    ws->ring_next[slot] = (r + 1) % ws->ring_depth;
+    if (ws->staged_pending[slot][r]) { /* an upload issued ring_depth calls ago may still read this buffer */
+        if (hipEventSynchronize(ws->staged[slot][r]) != hipSuccess) return AH_EHIP;
+        ws->staged_pending[slot][r] = false;
     }
-    memcpy(ws->h_stage[slot], tab.data(), tab.size() * sizeof(DevChunk));
-    if (hipMemcpyAsync(ws->d_tab[slot], ws->h_stage[slot], tab.size() * sizeof(DevChunk), hipMemcpyHostToDevice,
-                       stream) != hipSuccess)
+    memcpy(ws->h_stage[slot][r], tab.data(), tab.size() * sizeof(DevChunk));
+    if (hipMemcpyAsync(ws->d_tab[slot], ws->h_stage[slot][r], tab.size() * sizeof(DevChunk),
+                       hipMemcpyHostToDevice, stream) != hipSuccess)
         return AH_EHIP;
-    if (hipEventRecord(ws->staged[slot], stream) != hipSuccess) return AH_EHIP;
-    ws->staged_pending[slot] = true;
+    if (hipEventRecord(ws->staged[slot][r], stream) != hipSuccess) return AH_EHIP;
+    ws->staged_pending[slot][r] = true;
     last.swap(tab);
     return AH_OK;
 }
@@ -242,10 +250,12 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
     ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
     bool ok = true;
     const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
+    ws->ring_depth = (int)std::min<size_t>(autohete_ws::kRing, std::max<size_t>(1, (4u << 20) / tab_bytes));
     for (int s = 0; ok && s < 2; ++s) {
-        ok = hipMalloc(&ws->d_tab[s], tab_bytes) == hipSuccess &&
-             hipHostMalloc(&ws->h_stage[s], tab_bytes, hipHostMallocDefault) == hipSuccess &&
-             hipEventCreateWithFlags(&ws->staged[s], hipEventDisableTiming) == hipSuccess;
+        ok = hipMalloc(&ws->d_tab[s], tab_bytes) == hipSuccess;
+        for (int r = 0; ok && r < ws->ring_depth; ++r)
+            ok = hipHostMalloc(&ws->h_stage[s][r], tab_bytes, hipHostMallocDefault) == hipSuccess &&
+                 hipEventCreateWithFlags(&ws->staged[s][r], hipEventDisableTiming) == hipSuccess;
     }
     ok = ok && hipMalloc(&ws->d_partials, ah::kMaxPartials * sizeof(double)) == hipSuccess &&
          hipMalloc(&ws->d_ticket, 256) == hipSuccess && hipMalloc(&ws->d_res, 256) == hipSuccess &&
@@ -274,8 +284,10 @@ int autohete_ws_destroy(autohete_ws *ws)
     (void)hipDeviceSynchronize();
     for (int s = 0; s < 2; ++s) {
         if (ws->d_tab[s]) (void)hipFree(ws->d_tab[s]);
-        if (ws->h_stage[s]) (void)hipHostFree(ws->h_stage[s]);
-        if (ws->staged[s]) (void)hipEventDestroy(ws->staged[s]);
+        for (int r = 0; r < autohete_ws::kRing; ++r) {
+            if (ws->h_stage[s][r]) (void)hipHostFree(ws->h_stage[s][r]);
+            if (ws->staged[s][r]) (void)hipEventDestroy(ws->staged[s][r]);
+        }
     }
     if (ws->d_partials) (void)hipFree(ws->d_partials);
     if (ws->d_ticket) (void)hipFree(ws->d_ticket);
@@ -318,8 +330,8 @@ static int read_result(autohete_ws *ws, hipStream_t stream, double *sumsq, float
     return AH_OK;
 }
 
-int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
-                       float loss_scale, double extra_sumsq, void *stream_, float *norm_out,
+static int prep_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                       float loss_scale, double extra_sumsq, bool accumulate, void *stream_, float *norm_out,
                        uint32_t *found_inf_out)
 {
     if (!ws || (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16)) return AH_EINVAL;
@@ -342,11 +354,25 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     if (blocks > (uint64_t)ah::kMaxPartials) blocks = ah::kMaxPartials;
     if (blocks > tiles) blocks = tiles;
     if (ah::launch_prep(lowp_dtype, (unsigned)blocks, stream, ws->d_tab[0], (uint32_t)n_chunks, tiles,
-                        1.0 / (double)loss_scale, extra_sumsq, ws->d_partials, ws->d_ticket,
+                        1.0 / (double)loss_scale, extra_sumsq, accumulate, ws->d_partials, ws->d_ticket,
                         ws->d_res) != hipSuccess)
         return AH_EHIP;
     if (norm_out || found_inf_out) return read_result(ws, stream, nullptr, norm_out, found_inf_out);
     return AH_OK;
+}
+
+int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
+                       float loss_scale, double extra_sumsq, void *stream, float *norm_out,
+                       uint32_t *found_inf_out)
+{
+    return prep_common(ws, chunks, n_chunks, lowp_dtype, loss_scale, extra_sumsq, false, stream, norm_out,
+                       found_inf_out);
+}
+
+int autohete_grad_prep_accumulate(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
+                                  int lowp_dtype, float loss_scale, void *stream)
+{
+    return prep_common(ws, chunks, n_chunks, lowp_dtype, loss_scale, 0.0, true, stream, nullptr, nullptr);
 }
 
 static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,

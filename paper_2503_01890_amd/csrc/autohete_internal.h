@@ -56,7 +56,7 @@ hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned gri
 constexpr uint32_t kCastTileElems = 512;
 hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, hipStream_t stream, const DevChunk *tab);
 hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const DevChunk *tab, uint32_t n_chunks,
-                       uint64_t total_tiles, double inv_scale, double extra_sumsq, double *partials,
+                       uint64_t total_tiles, double inv_scale, double extra_sumsq, bool accumulate, double *partials,
                        uint32_t *ticket, GradResult *res);
 hipError_t launch_set_result(hipStream_t stream, GradResult *res, double sumsq, uint32_t found_inf);
 

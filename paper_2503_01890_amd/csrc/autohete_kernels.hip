@@ -308,7 +308,7 @@ __device__ __forceinline__ double block_sum(double x, double *lds4)
 template <int DT>
 __global__ void __launch_bounds__(kThreads)
 grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t total_tiles, double inv_scale,
-                 double extra_sumsq, double *partials, uint32_t *ticket, GradResult *res)
+                 double extra_sumsq, uint32_t accumulate, double *partials, uint32_t *ticket, GradResult *res)
 {
     constexpr int U = kPrepUnroll;
     constexpr uint32_t kSub = kThreads * kPrepVec;
@@ -375,8 +375,15 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
         s += __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s = block_sum(s, lds4);
     if (threadIdx.x == 0) {
-        const double total = s * inv_scale * inv_scale + extra_sumsq;
-        const bool bad = !__builtin_isfinite(total);
+        /* accumulate: fold this call into the result already in the workspace (gradient norm
+         * gathered block by block while the backward pass still runs) */
+        double total = s * inv_scale * inv_scale + extra_sumsq;
+        bool carried_flag = false;
+        if (accumulate) {
+            total += res->sumsq;
+            carried_flag = res->found_inf != 0;
+        }
+        const bool bad = carried_flag || !__builtin_isfinite(total);
         const double nd = bad ? __builtin_nan("") : sqrt(total);
         res->sumsq = total;
         res->norm_d = nd;
@@ -446,16 +453,16 @@ hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned gri
 }
 
 hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const DevChunk *tab, uint32_t n_chunks,
-                       uint64_t total_tiles, double inv_scale, double extra_sumsq, double *partials,
+                       uint64_t total_tiles, double inv_scale, double extra_sumsq, bool accumulate, double *partials,
                        uint32_t *ticket, GradResult *res)
 {
     if (blocks == 0) blocks = 1; /* no chunks: one block still publishes S = extra_sumsq */
     if (dtype == kFP16)
         hipLaunchKernelGGL(grad_prep_kernel<kFP16>, dim3(blocks), dim3(kThreads), 0, stream, tab, n_chunks,
-                           total_tiles, inv_scale, extra_sumsq, partials, ticket, res);
+                           total_tiles, inv_scale, extra_sumsq, accumulate ? 1u : 0u, partials, ticket, res);
     else
         hipLaunchKernelGGL(grad_prep_kernel<kBF16>, dim3(blocks), dim3(kThreads), 0, stream, tab, n_chunks,
-                           total_tiles, inv_scale, extra_sumsq, partials, ticket, res);
+                           total_tiles, inv_scale, extra_sumsq, accumulate ? 1u : 0u, partials, ticket, res);
     return hipGetLastError();
 }
 

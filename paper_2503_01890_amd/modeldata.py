@@ -51,6 +51,22 @@ class ModelData:
         idx = range(self.n_chunks) if indices is None else indices
         return binding.chunk_array([self.chunk_tuple(i, grad_set) for i in idx])
 
+    def range_tuples(self, start, end, grad_set=0):
+        """Descriptors covering flat elements [start, end) of equally sized chunks (element e lives in
+        chunk e // C at position e % C): one sub-chunk per chunk touched.  Used to address one
+        transformer block's slice of the model data; start and end must be multiples of 8 elements
+        so that every slice stays 16-byte aligned."""
+        C = self.numel[0]
+        assert all(n == C for n in self.numel) and start % 8 == 0 and end % 8 == 0 and start <= end
+        out = []
+        e = start
+        while e < end:
+            c, pos = divmod(e, C)
+            n = min(C - pos, end - e)
+            out.append(tuple(self.view(s, c, grad_set)[pos:pos + n].data_ptr() for s in STREAMS) + (n,))
+            e += n
+        return out
+
     def zero_(self):
         for t in list(self.slab.values()) + self.grad_sets:
             t.zero_()

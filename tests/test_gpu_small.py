@@ -369,3 +369,63 @@ def test_split_path_master_only_step_then_cast(dtype):
     t[1] += 2
     assert lib.autohete_cast_params(ws._h, B.chunk_array([t]), 1, dtype, s) == B.AH_EALIGN
     ws.close()
+
+
+def test_per_block_prep_accumulate_and_backward_order_stepping():
+    """One optimizer per transformer block (footnote to Eq. 5): the norm is gathered block by block
+    with autohete_grad_prep_accumulate, and each block's slice of the flat model data -- sub-ranges
+    of chunks, tensors straddle chunk boundaries -- is stepped on its own, last block first, on a
+    second stream.  Must equal the one-shot path bit for bit given the same norm, and the oracle."""
+    import synthdata
+    d, L, C = 256, 3, 1 << 16
+    sizes = [int(x) for x in synthdata.gpt_tensor_numel(d, L, 1000, 64)]
+    off, n_chunks, total, pad = B.autohete_chunk_layout(sizes, C)
+    # partitions: embedding + positions, then 12 tensors per layer (flat element ranges)
+    bounds = [0, off[2]] + [off[2 + 12 * (i + 1)] if 2 + 12 * (i + 1) < len(off) else total for i in range(L)]
+    blocks = list(zip(bounds[:-1], bounds[1:]))
+    assert blocks[-1][1] == total and all(a % 8 == 0 and b % 8 == 0 for a, b in blocks)
+    rng = np.random.default_rng(5)
+    states = [random_state(C, B.AH_BF16, rng) for _ in range(n_chunks)]
+    for k in states[-1]:
+        states[-1][k][C - pad:] = 0
+    hp = B.hparams(max_grad_norm=0.05)
+    per_block, one_shot = ModelData([C] * n_chunks), ModelData([C] * n_chunks)
+    for i, st in enumerate(states):
+        upload(per_block, i, st)
+        upload(one_shot, i, st)
+    ws = B.Workspace(n_chunks + 2)
+    side = torch.cuda.Stream()                      # default priority
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        s = side.cuda_stream
+        ws.autohete_grad_result_set(0.0, 0, s)
+        for a, b in reversed(blocks):               # gradients "land" last block first
+            tup = per_block.range_tuples(a, b)
+            ws.autohete_grad_prep_accumulate(B.chunk_array(tup), len(tup), B.AH_BF16, 1.0, s)
+        sumsq, norm, flag = ws.autohete_grad_result_get(s)
+        for a, b in reversed(blocks):
+            tup = per_block.range_tuples(a, b)
+            ws.autohete_adamw_step(B.chunk_array(tup), len(tup), B.AH_BF16, 2, hp, s)
+    side.synchronize()
+    assert flag == 0
+    ref = sum(float(np.sum(oracle.decode(st["grad"], oracle.BF16).astype(np.float64) ** 2)) for st in states)
+    assert abs(sumsq - ref) <= 1e-12 * ref
+    ws.autohete_grad_result_set(sumsq, 0, stream_handle())          # same norm -> must be bit-identical
+    ws.autohete_adamw_step(one_shot.chunk_array(), n_chunks, B.AH_BF16, 2, hp, stream_handle())
+    torch.cuda.synchronize()
+    for i in range(n_chunks):
+        a, b = download(per_block, i), download(one_shot, i)
+        assert all(a[k].tobytes() == b[k].tobytes() for k in STREAMS), i
+    run_oracle(states, oracle.BF16, 2, hp)
+    for i, st in enumerate(states):
+        compare_state(download(per_block, i), st, "per-block chunk=%d" % i, st["old"])
+    # a non-finite gradient in ANY block keeps the flag through later accumulations
+    bad = states[1]["grad"].copy()
+    bad[17] = 0x7F80
+    upload(per_block, 1, dict(grad=bad))
+    ws.autohete_grad_result_set(0.0, 0, stream_handle())
+    for a, b in blocks:
+        tup = per_block.range_tuples(a, b)
+        ws.autohete_grad_prep_accumulate(B.chunk_array(tup), len(tup), B.AH_BF16, 1.0, stream_handle())
+    assert ws.autohete_grad_result_get(stream_handle())[2] == 1
+    ws.close()
