@@ -44,7 +44,8 @@ enum {
     AH_EINVAL = -1, /* null pointer, bad enum, numel == 0, step == 0, bad hyper-parameter */
     AH_EALIGN = -2, /* a device pointer is not 16-byte aligned */
     AH_ENOMEM = -3, /* allocation failed, or more chunks than the workspace was made for */
-    AH_EHIP = -4    /* a HIP runtime call failed */
+    AH_EHIP = -4,   /* a HIP runtime call failed */
+    AH_EINFEASIBLE = -5 /* autohete_strategy_search: no strategy satisfies the memory constraints */
 };
 
 enum { AH_BF16 = 0, AH_FP16 = 1 }; /* format of the two 16-bit streams */
@@ -188,6 +189,48 @@ enum {
                                        0 = default                                             */
 };
 int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value);
+
+/*
+ * Cost model and strategy search (host only; paper section 3.2.2, Eq. 1-6).  The planning unit is
+ * the transformer block; a strategy is (c, p, o) = how many blocks use activation checkpointing
+ * and parameter offloading (the first c and p blocks: Insight 1) and optimizer-state offloading
+ * (the last o blocks: Insight 2).  Sizes are in ELEMENTS where the paper writes M (it multiplies
+ * by 2, 12 or 14 bytes itself), capacities and constants in bytes, times per block in any one
+ * unit.  t_optim_gpu is the quantity this library's benchmark measures.
+ *   autohete_strategy_eval    fills every field of *out for one (c, p, o); feasible = Eq. 1 and
+ *                             Eq. 2 hold and p <= o.  AH_EINVAL if a count exceeds n_blocks.
+ *   autohete_strategy_search  exact minimum of t_fwd + t_bwd over the feasible points (Eq. 6);
+ *                             ties go to the smallest o, then p, then c.  AH_EINFEASIBLE if none.
+ * AH_EINVAL for NULL pointers, n_blocks outside 1..4096, negative or non-finite inputs, or
+ * act_in_elems > act_elems.
+ */
+typedef struct {
+    uint32_t n_blocks;          /* L */
+    double act_elems;           /* M_a : activations of one block */
+    double act_in_elems;        /* M_a': its input activations (what checkpointing keeps) */
+    double param_elems;         /* M_p : parameters of one block */
+    double gpu_const_bytes;     /* M_gc */
+    double cpu_const_bytes;     /* M_cc */
+    double gpu_capacity_bytes;  /* M_gpu */
+    double cpu_capacity_bytes;  /* M_cpu */
+    double t_fp, t_bp;          /* forward / backward compute of one block */
+    double t_h2d, t_d2h;        /* 16-bit parameter prefetch / gradient (or parameter) offload of one block */
+    double t_optim_cpu, t_optim_gpu; /* optimizer update of one block on the host / on the GPU */
+} autohete_cost_model;
+
+typedef struct {
+    uint32_t n_ckpt, n_param_offload, n_optim_offload; /* c, p, o */
+    int feasible;
+    double gpu_bytes;           /* left side of Eq. 1 */
+    double cpu_bytes;           /* left side of Eq. 2 */
+    double t_fwd;               /* Eq. 3 */
+    double t_sync;              /* Eq. 4 */
+    double t_bwd;               /* Eq. 5 */
+} autohete_strategy;
+
+int autohete_strategy_eval(const autohete_cost_model *model, uint32_t n_ckpt, uint32_t n_param_offload,
+                           uint32_t n_optim_offload, autohete_strategy *out);
+int autohete_strategy_search(const autohete_cost_model *model, autohete_strategy *best);
 
 const char *autohete_strerror(int status);
 

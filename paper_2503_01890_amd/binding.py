@@ -10,7 +10,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libautohete.so")
 
-AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP = 0, -1, -2, -3, -4
+AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP, AH_EINFEASIBLE = 0, -1, -2, -3, -4, -5
 AH_BF16, AH_FP16 = 0, 1
 AH_TUNE_STEP_BLOCKS_PER_CU, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT = 0, 1, 2
 
@@ -42,6 +42,18 @@ class autohete_chunk(ctypes.Structure):
 class autohete_hparams(ctypes.Structure):
     _fields_ = [(k, ctypes.c_float) for k in
                 ("lr", "beta1", "beta2", "eps", "weight_decay", "max_grad_norm", "loss_scale")]
+
+
+class autohete_cost_model(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_uint32)] + [(k, ctypes.c_double) for k in (
+        "act_elems", "act_in_elems", "param_elems", "gpu_const_bytes", "cpu_const_bytes", "gpu_capacity_bytes",
+        "cpu_capacity_bytes", "t_fp", "t_bp", "t_h2d", "t_d2h", "t_optim_cpu", "t_optim_gpu")]
+
+
+class autohete_strategy(ctypes.Structure):
+    _fields_ = [("n_ckpt", ctypes.c_uint32), ("n_param_offload", ctypes.c_uint32), ("n_optim_offload", ctypes.c_uint32),
+                ("feasible", ctypes.c_int), ("gpu_bytes", ctypes.c_double), ("cpu_bytes", ctypes.c_double),
+                ("t_fwd", ctypes.c_double), ("t_sync", ctypes.c_double), ("t_bwd", ctypes.c_double)]
 
 
 class AutoheteError(RuntimeError):
@@ -83,6 +95,13 @@ _lib.autohete_grad_result_set.restype = ctypes.c_int
 _lib.autohete_grad_result_set.argtypes = [ctypes.c_void_p, ctypes.c_double, ctypes.c_uint32, ctypes.c_void_p]
 
 
+_lib.autohete_strategy_eval.restype = ctypes.c_int
+_lib.autohete_strategy_eval.argtypes = [ctypes.POINTER(autohete_cost_model), ctypes.c_uint32, ctypes.c_uint32,
+                                        ctypes.c_uint32, ctypes.POINTER(autohete_strategy)]
+_lib.autohete_strategy_search.restype = ctypes.c_int
+_lib.autohete_strategy_search.argtypes = [ctypes.POINTER(autohete_cost_model), ctypes.POINTER(autohete_strategy)]
+
+
 def _check(rc, where):
     if rc != AH_OK:
         raise AutoheteError(rc, where)
@@ -97,6 +116,19 @@ def autohete_chunk_layout(tensor_numel, chunk_elems):
     _check(_lib.autohete_chunk_layout(numel, n, int(chunk_elems), off, ctypes.byref(nc), ctypes.byref(tot),
                                       ctypes.byref(pad)), "autohete_chunk_layout")
     return list(off[:n]), nc.value, tot.value, pad.value
+
+
+def autohete_strategy_eval(model, n_ckpt, n_param_offload, n_optim_offload):
+    out = autohete_strategy()
+    _check(_lib.autohete_strategy_eval(ctypes.byref(model), n_ckpt, n_param_offload, n_optim_offload,
+                                       ctypes.byref(out)), "autohete_strategy_eval")
+    return out
+
+
+def autohete_strategy_search(model):
+    out = autohete_strategy()
+    _check(_lib.autohete_strategy_search(ctypes.byref(model), ctypes.byref(out)), "autohete_strategy_search")
+    return out
 
 
 def chunk_array(chunks):

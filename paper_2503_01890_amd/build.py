@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libautohete.so")
-SOURCES = ["autohete_api.hip", "autohete_kernels.hip"]
+SOURCES = ["autohete_api.hip", "autohete_kernels.hip", "autohete_strategy.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
          # hipcc -O3 must not form packed-fp32 instructions on the test machines

@@ -211,6 +211,7 @@ const char *autohete_strerror(int status)
         case AH_EALIGN: return "device pointer not 16-byte aligned";
         case AH_ENOMEM: return "out of memory or more chunks than the workspace holds";
         case AH_EHIP: return "HIP runtime error";
+        case AH_EINFEASIBLE: return "no strategy satisfies the memory constraints";
         default: return "unknown status";
     }
 }
