@@ -191,6 +191,32 @@ enum {
 int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value);
 
 /*
+ * Host half of a hybrid placement (paper section 3.2.1: a block whose optimizer states are placed on
+ * the CPU has its 16-bit gradients offloaded and its fp32 parameters updated there; cost
+ * t_optim^cpu, Eq. 5 second arm).  Same rule, same fp64 arithmetic and rounding as the GPU kernels,
+ * on chunks whose five pointers are HOST pointers (any alignment); multi-threaded, AVX-512 where
+ * the CPU has it.  Both calls are synchronous.
+ *   autohete_host_grad_sumsq   *sumsq = sum (grad / loss_scale)^2 over the chunks (only .grad and
+ *                              .numel are used), *found_inf = 1 if any gradient is non-finite.
+ *                              Add it to the device-side sum through extra_sumsq, or the other way.
+ *   autohete_host_adamw_step   the update with the GLOBAL sum of squares `sumsq` and skip flag
+ *                              given by the caller (nothing is touched when the flag is set or
+ *                              sumsq is non-finite); .param_lp may be NULL (no 16-bit write-back).
+ *                              .grad and .param_lp may be the SAME buffer (on the host the two never
+ *                              coexist, Eq. 2: 14 bytes per parameter): each element's gradient is
+ *                              read before its parameter is written.
+ *   n_threads                  1..1024 worker threads; results do not depend on it except the
+ *                              last bits of *sumsq.
+ *   autohete_host_force_scalar test hook: non-zero disables the AVX-512 path (same results).
+ * Errors: AH_EINVAL (as for the device calls), AH_ENOMEM (threads could not be started).
+ */
+int autohete_host_grad_sumsq(const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype, float loss_scale,
+                             int n_threads, double *sumsq, uint32_t *found_inf);
+int autohete_host_adamw_step(const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype, uint64_t step,
+                             const autohete_hparams *hp, double sumsq, uint32_t found_inf, int n_threads);
+int autohete_host_force_scalar(int on);
+
+/*
  * Cost model and strategy search (host only; paper section 3.2.2, Eq. 1-6).  The planning unit is
  * the transformer block; a strategy is (c, p, o) = how many blocks use activation checkpointing
  * and parameter offloading (the first c and p blocks: Insight 1) and optimizer-state offloading

@@ -102,6 +102,18 @@ _lib.autohete_strategy_search.restype = ctypes.c_int
 _lib.autohete_strategy_search.argtypes = [ctypes.POINTER(autohete_cost_model), ctypes.POINTER(autohete_strategy)]
 
 
+_lib.autohete_host_grad_sumsq.restype = ctypes.c_int
+_lib.autohete_host_grad_sumsq.argtypes = [ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int, ctypes.c_float,
+                                          ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_uint32)]
+_lib.autohete_host_adamw_step.restype = ctypes.c_int
+_lib.autohete_host_adamw_step.argtypes = [ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int, ctypes.c_uint64,
+                                          ctypes.POINTER(autohete_hparams), ctypes.c_double, ctypes.c_uint32,
+                                          ctypes.c_int]
+_lib.autohete_host_force_scalar.restype = ctypes.c_int
+_lib.autohete_host_force_scalar.argtypes = [ctypes.c_int]
+
+
 def _check(rc, where):
     if rc != AH_OK:
         raise AutoheteError(rc, where)
@@ -129,6 +141,19 @@ def autohete_strategy_search(model):
     out = autohete_strategy()
     _check(_lib.autohete_strategy_search(ctypes.byref(model), ctypes.byref(out)), "autohete_strategy_search")
     return out
+
+
+def autohete_host_grad_sumsq(chunks, n_chunks, lowp_dtype, loss_scale, n_threads):
+    """chunks: array from chunk_array() holding HOST addresses.  -> (sumsq, found_inf)"""
+    s, f = ctypes.c_double(), ctypes.c_uint32()
+    _check(_lib.autohete_host_grad_sumsq(chunks, n_chunks, lowp_dtype, loss_scale, n_threads, ctypes.byref(s),
+                                         ctypes.byref(f)), "autohete_host_grad_sumsq")
+    return s.value, f.value
+
+
+def autohete_host_adamw_step(chunks, n_chunks, lowp_dtype, step, hp, sumsq, found_inf, n_threads):
+    _check(_lib.autohete_host_adamw_step(chunks, n_chunks, lowp_dtype, int(step), ctypes.byref(hp), float(sumsq),
+                                         int(found_inf), n_threads), "autohete_host_adamw_step")
 
 
 def chunk_array(chunks):

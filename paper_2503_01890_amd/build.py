@@ -5,9 +5,9 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libautohete.so")
-SOURCES = ["autohete_api.hip", "autohete_kernels.hip", "autohete_strategy.cpp"]
+SOURCES = ["autohete_api.hip", "autohete_kernels.hip", "autohete_strategy.cpp", "autohete_host.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
          # hipcc -O3 must not form packed-fp32 instructions on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

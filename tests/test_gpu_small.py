@@ -429,3 +429,57 @@ def test_per_block_prep_accumulate_and_backward_order_stepping():
         ws.autohete_grad_prep_accumulate(B.chunk_array(tup), len(tup), B.AH_BF16, 1.0, stream_handle())
     assert ws.autohete_grad_result_get(stream_handle())[2] == 1
     ws.close()
+
+
+def test_hybrid_placement_step_matches_oracle():
+    """Half of the chunks resident (GPU kernels), half host-owned (gradients D2H -> host AdamW ->
+    16-bit parameters H2D through one pinned buffer per chunk): two steps against the oracle."""
+    from paper_2503_01890_amd.hybrid import HostChunks, HybridStepper
+    C, n_res, n_host = 1 << 16, 3, 3
+    rng = np.random.default_rng(41)
+    states = [random_state(C, B.AH_BF16, rng) for _ in range(n_res + n_host)]
+    md = ModelData([C] * n_res)
+    for i in range(n_res):
+        upload(md, i, states[i])
+    host = HostChunks(n_host, C)
+    for c in range(n_host):
+        st = states[n_res + c]
+        host.master[c][:] = st["master"]
+        host.exp_avg[c][:] = st["exp_avg"]
+        host.exp_avg_sq[c][:] = st["exp_avg_sq"]
+        host.dev_view("param_lp", c).copy_(torch.from_numpy(st["param_lp"].view(np.int16)))
+    stepper = HybridStepper(md, host, B.AH_BF16, n_threads=4)
+    hp = B.hparams(max_grad_norm=0.05)
+    for step in (1, 2):
+        for i, st in enumerate(states):
+            st["grad"] = random_state(C, B.AH_BF16, rng)["grad"]
+            if i < n_res:
+                upload(md, i, dict(grad=st["grad"]))
+            else:
+                host.dev_view("grad", i - n_res).copy_(torch.from_numpy(st["grad"].view(np.int16)))
+        torch.cuda.synchronize()
+        out = stepper.step(step, hp)
+        on, of = run_oracle(states, oracle.BF16, step, hp)
+        assert out["found_inf"] == of == 0 and abs(out["norm"] - on) <= 1e-5 * on
+        for i, st in enumerate(states):
+            if i < n_res:
+                got = download(md, i)
+            else:
+                c = i - n_res
+                got = dict(master=host.master[c], exp_avg=host.exp_avg[c], exp_avg_sq=host.exp_avg_sq[c],
+                           param_lp=host.dev_view("param_lp", c).cpu().numpy().view(np.uint16))
+            compare_state(got, st, "hybrid step=%d chunk=%d" % (step, i), st["old"], drift_steps=step - 1)
+    # overflow in a HOST-owned gradient: the GPU's norm sees it, both halves skip
+    bad = states[n_res + 1]["grad"].copy()
+    bad[99] = 0x7F80
+    host.dev_view("grad", 1).copy_(torch.from_numpy(bad.view(np.int16)))
+    keep_master = [m.copy() for m in host.master]
+    keep_lp = host.dev_param_lp.clone()
+    keep_res = [download(md, i) for i in range(n_res)]
+    out = stepper.step(3, hp)
+    assert out["found_inf"] == 1
+    assert all(np.array_equal(a, b) for a, b in zip(keep_master, host.master)) and torch.equal(keep_lp, host.dev_param_lp)
+    for i in range(n_res):
+        now = download(md, i)
+        assert all(now[k].tobytes() == keep_res[i][k].tobytes() for k in STREAMS)
+    stepper.close()

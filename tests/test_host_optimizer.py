@@ -1,0 +1,124 @@
+"""Host half of the hybrid placement (autohete_host_*): the library's CPU AdamW against the oracle.
+Both compute in fp64 in the same operation order, so given the same global sum of squares the
+results must be bit-identical -- AVX-512 path and scalar path, any thread count, both formats,
+ragged sizes.  Runs without a GPU."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_01890_amd import binding as B
+
+RNG = np.random.default_rng(99)
+
+
+def lowp(x, dtype):
+    return oracle.encode(np.asarray(x, np.float32), dtype)           # inputs only; pinned elsewhere
+
+
+def make_state(n, dtype, scale=1.0):
+    p16 = lowp(RNG.normal(0, 0.02, n), dtype)
+    return dict(grad=lowp(RNG.normal(0, 1e-3, n) * scale, dtype), param_lp=p16.copy(), master=oracle.decode(p16, dtype),
+                exp_avg=RNG.normal(0, 1e-4, n).astype(np.float32),
+                exp_avg_sq=np.abs(RNG.normal(0, 1e-6, n)).astype(np.float32))
+
+
+def host_chunks(states, with_lp=True):
+    return B.chunk_array([(st["grad"].ctypes.data, st["param_lp"].ctypes.data if with_lp else None,
+                           st["master"].ctypes.data, st["exp_avg"].ctypes.data, st["exp_avg_sq"].ctypes.data,
+                           st["grad"].size) for st in states])
+
+
+@pytest.fixture(params=[0, 1], ids=["avx512", "scalar"])
+def simd(request):
+    B.raw().autohete_host_force_scalar(request.param)
+    yield request.param
+    B.raw().autohete_host_force_scalar(0)
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+@pytest.mark.parametrize("threads", [1, 3, 8])
+def test_host_step_is_bit_identical_to_the_oracle(simd, dtype, threads):
+    scale = 1.0 if dtype == B.AH_BF16 else 512.0
+    numels = [1, 7, 8, 9, 15, 16, 17, 1000, 4099, 65536 + 3]
+    lib_states = [make_state(n, dtype, scale) for n in numels]
+    ora_states = [{k: v.copy() for k, v in st.items()} for st in lib_states]
+    hp, ohp = B.hparams(loss_scale=scale, max_grad_norm=0.05), oracle.hparams(loss_scale=scale, max_grad_norm=0.05)
+    arr = host_chunks(lib_states)
+    for step in (1, 2, 3):
+        sumsq, flag = B.autohete_host_grad_sumsq(arr, len(numels), dtype, scale, threads)
+        onorm, oflag = oracle.grad_prep([st["grad"] for st in ora_states], dtype, scale)
+        assert flag == oflag == 0 and abs(np.sqrt(sumsq) - onorm) <= 1e-13 * onorm
+        # same global sum on both sides (the oracle's) -> every stored bit must agree
+        B.autohete_host_adamw_step(arr, len(numels), dtype, step, hp, onorm * onorm, 0, threads)
+        for st in ora_states:
+            oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], dtype, step,
+                               ohp, np.sqrt(onorm * onorm), 0)
+        for a, b in zip(lib_states, ora_states):
+            for k in a:
+                assert a[k].tobytes() == b[k].tobytes(), (step, k, a[k].size)
+
+
+def test_host_skip_nonfinite_and_no_writeback(simd):
+    st = make_state(5000, B.AH_BF16)
+    st["grad"][4321] = 0x7F80
+    arr = host_chunks([st])
+    sumsq, flag = B.autohete_host_grad_sumsq(arr, 1, B.AH_BF16, 1.0, 4)
+    assert flag == 1 and not np.isfinite(sumsq)
+    before = {k: v.copy() for k, v in st.items()}
+    B.autohete_host_adamw_step(arr, 1, B.AH_BF16, 1, B.hparams(), sumsq, flag, 4)
+    B.autohete_host_adamw_step(arr, 1, B.AH_BF16, 1, B.hparams(), 1.0, 1, 4)
+    assert all(st[k].tobytes() == before[k].tobytes() for k in st)
+    # NaN gradient, and no 16-bit write-back when param_lp is NULL
+    st["grad"][4321] = 0x7FC0
+    assert B.autohete_host_grad_sumsq(arr, 1, B.AH_BF16, 1.0, 2)[1] == 1
+    st["grad"][4321] = 0
+    stale = st["param_lp"].copy()
+    ref = {k: v.copy() for k, v in st.items()}
+    B.autohete_host_adamw_step(host_chunks([st], with_lp=False), 1, B.AH_BF16, 2, B.hparams(), 0.25, 0, 5)
+    oracle.adamw_chunk(ref["grad"], None, ref["master"], ref["exp_avg"], ref["exp_avg_sq"], oracle.BF16, 2,
+                       oracle.hparams(), 0.5, 0)
+    assert np.array_equal(st["param_lp"], stale)
+    assert all(st[k].tobytes() == ref[k].tobytes() for k in ("master", "exp_avg", "exp_avg_sq"))
+
+
+def test_host_16bit_conversions_cover_edge_values(simd):
+    """Write-back through the host path on values chosen for the format edges (ties, overflow to inf,
+    subnormals): lr = 0, wd = 0 keeps master unchanged, so param_lp = RNE(master)."""
+    for dtype in (B.AH_BF16, B.AH_FP16):
+        vals = np.concatenate([RNG.normal(0, 1, 4000), [0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e-8, 6e-8, -3e-8, 3e38],
+                               np.float32(1.0) + np.arange(0, 64) * np.float32(2.0 ** -12),
+                               np.arange(0, 40) * np.float32(0.5 * 2.0 ** -24)]).astype(np.float32)
+        n = vals.size
+        st = dict(grad=np.zeros(n, np.uint16), param_lp=np.zeros(n, np.uint16), master=vals.copy(),
+                  exp_avg=np.zeros(n, np.float32), exp_avg_sq=np.zeros(n, np.float32))
+        B.autohete_host_adamw_step(host_chunks([st]), 1, dtype, 1, B.hparams(lr=0.0, weight_decay=0.0), 0.0, 0, 3)
+        assert np.array_equal(st["master"], vals)
+        assert np.array_equal(st["param_lp"], oracle.encode(vals, dtype))
+        # and the decode side: the norm of every finite 16-bit pattern
+        bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+        x = oracle.decode(bits, dtype).astype(np.float64)
+        bits = bits[np.isfinite(x)]
+        x = x[np.isfinite(x)]
+        g = dict(st, grad=bits.copy())
+        arr = B.chunk_array([(g["grad"].ctypes.data, None, None, None, None, bits.size)])
+        sumsq, flag = B.autohete_host_grad_sumsq(arr, 1, dtype, 1.0, 2)
+        assert flag == 0 and sumsq == pytest.approx(float(np.sum(x * x)), rel=1e-13)
+
+
+def test_host_errors():
+    st = make_state(64, B.AH_BF16)
+    arr = host_chunks([st])
+    lib = B.raw()
+    hp = B.hparams()
+    s, f = ctypes.c_double(), ctypes.c_uint32()
+    assert lib.autohete_host_grad_sumsq(arr, 1, B.AH_BF16, ctypes.c_float(1.0), 0, ctypes.byref(s), ctypes.byref(f)) == B.AH_EINVAL
+    assert lib.autohete_host_grad_sumsq(arr, 1, 5, ctypes.c_float(1.0), 1, ctypes.byref(s), ctypes.byref(f)) == B.AH_EINVAL
+    assert lib.autohete_host_grad_sumsq(arr, 1, B.AH_BF16, ctypes.c_float(0.0), 1, ctypes.byref(s), ctypes.byref(f)) == B.AH_EINVAL
+    assert lib.autohete_host_grad_sumsq(arr, 1, B.AH_BF16, ctypes.c_float(1.0), 1, None, ctypes.byref(f)) == B.AH_EINVAL
+    assert lib.autohete_host_adamw_step(arr, 1, B.AH_BF16, 0, ctypes.byref(hp), 1.0, 0, 1) == B.AH_EINVAL
+    bad = B.hparams(beta1=1.0)
+    assert lib.autohete_host_adamw_step(arr, 1, B.AH_BF16, 1, ctypes.byref(bad), 1.0, 0, 1) == B.AH_EINVAL
+    nul = B.chunk_array([(st["grad"].ctypes.data, None, None, st["exp_avg"].ctypes.data, st["exp_avg_sq"].ctypes.data, 64)])
+    assert lib.autohete_host_adamw_step(nul, 1, B.AH_BF16, 1, ctypes.byref(hp), 1.0, 0, 1) == B.AH_EINVAL
