@@ -183,6 +183,7 @@ enum {
     AH_TUNE_STEP_BLOCKS_PER_CU = 0, /* cap on step-kernel blocks resident per CU (1..64; 64 =
                                        no cap); 0 = default                                    */
     AH_TUNE_PREP_BLOCKS = 1,        /* thread blocks of the prep kernel; 0 = default           */
+    AH_TUNE_CAST_BLOCKS_PER_CU = 3, /* the same cap for the cast kernel; 0 = default           */
     AH_TUNE_STEP_VARIANT = 2        /* step-kernel variant: elements per lane (1, 2, 4)
                                        | mode << 4 (0 = fp64 Newton root/quotient, 1 = fp64
                                        correctly rounded) | (threads per block / 64) << 8;

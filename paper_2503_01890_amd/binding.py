@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libautohete.so")
 
 AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP, AH_EINFEASIBLE = 0, -1, -2, -3, -4, -5
 AH_BF16, AH_FP16 = 0, 1
-AH_TUNE_STEP_BLOCKS_PER_CU, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT = 0, 1, 2
+AH_TUNE_STEP_BLOCKS_PER_CU, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT, AH_TUNE_CAST_BLOCKS_PER_CU = 0, 1, 2, 3
 
 
 def step_variant(vec=4, block=64, mode=0):

@@ -37,7 +37,7 @@ struct autohete_ws {
     uint32_t *d_ticket = nullptr;
     GradResult *d_res = nullptr;
     GradResult *h_res = nullptr;                /* pinned read-back */
-    int64_t tune_step_blocks_per_cu = 0, tune_prep_blocks = 0, tune_step_variant = 0;
+    int64_t tune_step_blocks_per_cu = 0, tune_prep_blocks = 0, tune_step_variant = 0, tune_cast_blocks_per_cu = 0;
     size_t lds_per_cu = 0;
     /* launch groups of the current step table: rows [first, first+rows) share grid_x */
     struct Group { uint32_t first, rows; uint64_t max_tiles; };
@@ -50,6 +50,7 @@ namespace {
  * Default: 4 elements per lane, one wavefront per block, Newton fp64, at most 10 blocks per CU. */
 constexpr int64_t kDefaultVariant = 4 | (0 << 4) | (1 << 8);
 constexpr int kDefaultBlocksPerCu = 10;
+constexpr int kDefaultCastBlocksPerCu = 24; /* measured: 64 -> 6.38, 24 -> 6.88, 16 -> 6.10 TB/s */
 
 bool decode_variant(int64_t v, ah::StepVariant *out)
 {
@@ -184,6 +185,16 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
     return AH_OK;
 }
 
+/* Cap on resident blocks per CU, enforced through the dynamic LDS request: the launcher asks for
+ * 1/cap of a CU's LDS per block (the kernels themselves use none).  cap >= 64: no request. */
+unsigned lds_for_cap(const autohete_ws *ws, int64_t cap)
+{
+    if (cap >= 64 || !ws->lds_per_cu) return 0;
+    size_t want = ws->lds_per_cu / (size_t)cap;
+    want = want > 1024 ? want - 512 : want; /* stay clear of allocation-granule rounding */
+    return (unsigned)std::min<size_t>(want, 64 * 1024);
+}
+
 struct DeviceGuard { /* run on the workspace's device, restore the caller's afterwards */
     int prev = -1;
     bool ok = false;
@@ -306,6 +317,10 @@ int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value)
             if (value > 64) return AH_EINVAL;
             ws->tune_step_blocks_per_cu = value;
             return AH_OK;
+        case AH_TUNE_CAST_BLOCKS_PER_CU:
+            if (value > 64) return AH_EINVAL;
+            ws->tune_cast_blocks_per_cu = value;
+            return AH_OK;
         case AH_TUNE_PREP_BLOCKS:
             if (value > ah::kMaxPartials) return AH_EINVAL;
             ws->tune_prep_blocks = value;
@@ -417,15 +432,8 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     k.eps = (double)hp->eps;
     k.wd = (double)hp->weight_decay;
 
-    /* Cap on resident blocks per CU, enforced through the dynamic LDS request: the launcher asks
-     * for 1/cap of a CU's LDS per block (the kernel itself uses none). */
-    const int64_t cap = ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu : kDefaultBlocksPerCu;
-    unsigned lds = 0;
-    if (cap < 64 && ws->lds_per_cu) {
-        size_t want = ws->lds_per_cu / (size_t)cap;
-        want = want > 1024 ? want - 512 : want;          /* stay clear of allocation-granule rounding */
-        lds = (unsigned)std::min<size_t>(want, 64 * 1024);
-    }
+    const unsigned lds = lds_for_cap(ws, ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu
+                                                                      : kDefaultBlocksPerCu);
     for (const autohete_ws::Group &grp : ws->step_groups) {
         if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
                             ws->d_tab[1] + grp.first, ws->d_res, k) != hipSuccess)
@@ -460,8 +468,10 @@ int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t
         return AH_ENOMEM;
     }
     if (rc != AH_OK) return rc;
+    const unsigned lds = lds_for_cap(ws, ws->tune_cast_blocks_per_cu ? ws->tune_cast_blocks_per_cu
+                                                                      : kDefaultCastBlocksPerCu);
     for (const autohete_ws::Group &grp : ws->step_groups) {
-        if (ah::launch_cast(lowp_dtype, (unsigned)grp.max_tiles, grp.rows, stream, ws->d_tab[1] + grp.first) !=
+        if (ah::launch_cast(lowp_dtype, (unsigned)grp.max_tiles, grp.rows, lds, stream, ws->d_tab[1] + grp.first) !=
             hipSuccess)
             return AH_EHIP;
     }

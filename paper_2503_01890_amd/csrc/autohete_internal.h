@@ -54,7 +54,8 @@ hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned gri
                        hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k);
 /* master -> 16-bit conversion: grid_x tiles of 512 elements for each of grid_y table rows */
 constexpr uint32_t kCastTileElems = 512;
-hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, hipStream_t stream, const DevChunk *tab);
+hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, unsigned lds_bytes, hipStream_t stream,
+                       const DevChunk *tab);
 hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const DevChunk *tab, uint32_t n_chunks,
                        uint64_t total_tiles, double inv_scale, double extra_sumsq, bool accumulate, double *partials,
                        uint32_t *ticket, GradResult *res);

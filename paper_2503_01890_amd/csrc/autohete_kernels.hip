@@ -432,13 +432,14 @@ static step_fn pick_step(int dtype, StepVariant s)
 
 bool step_variant_valid(StepVariant s) { return pick_step(kBF16, s) != nullptr; }
 
-hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, hipStream_t stream, const DevChunk *tab)
+hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, unsigned lds_bytes, hipStream_t stream,
+                       const DevChunk *tab)
 {
     if (grid_x == 0 || grid_y == 0) return hipSuccess;
     if (dtype == kFP16)
-        hipLaunchKernelGGL(cast_params_kernel<kFP16>, dim3(grid_x, grid_y), dim3(64), 0, stream, tab);
+        hipLaunchKernelGGL(cast_params_kernel<kFP16>, dim3(grid_x, grid_y), dim3(64), lds_bytes, stream, tab);
     else
-        hipLaunchKernelGGL(cast_params_kernel<kBF16>, dim3(grid_x, grid_y), dim3(64), 0, stream, tab);
+        hipLaunchKernelGGL(cast_params_kernel<kBF16>, dim3(grid_x, grid_y), dim3(64), lds_bytes, stream, tab);
     return hipGetLastError();
 }
 

@@ -76,3 +76,10 @@ def test_model_data_byte_accounting():
     from paper_2503_01890_amd import modeldata
     per = {"grad": 2, "param_lp": 2, "master": 4, "exp_avg": 4, "exp_avg_sq": 4}
     assert set(per) == set(modeldata.STREAMS) and sum(per.values()) == 16
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr

@@ -483,3 +483,60 @@ def test_hybrid_placement_step_matches_oracle():
         now = download(md, i)
         assert all(now[k].tobytes() == keep_res[i][k].tobytes() for k in STREAMS)
     stepper.close()
+
+
+def test_single_chunk_beyond_2_to_32_elements():
+    """64-bit indexing: ONE chunk of 2^32 + 2^20 + 24 elements (68.8 GB of model data).  The norm is
+    checked over every element; the update on windows at the start, across element 2^32 and at the
+    ragged end, regenerated on the CPU from the same seeds."""
+    import synthdata
+    from _harness import N_THREADS
+    import concurrent.futures as cf
+    n = (1 << 32) + (1 << 20) + 24
+    free, _ = torch.cuda.mem_get_info()
+    if free < n * 16 + (8 << 30):
+        pytest.skip("not enough free HBM for a 69 GB chunk")
+    w = synthdata.Workload("huge-chunk", [n], n)          # one tensor, one chunk, no padding
+    assert w.n_chunks == 1
+    md = ModelData([n])
+    st = stream_handle()
+    synthdata.fill_gpu(md.ptr("param_lp", 0), n, w.spec_param_lp(0), st)
+    synthdata.fill_gpu(md.ptr("master", 0), n, w.spec_master(0), st)
+    synthdata.fill_gpu(md.ptr("exp_avg", 0), n, w.spec_exp_avg(0), st)
+    synthdata.fill_gpu(md.ptr("exp_avg_sq", 0), n, w.spec_exp_avg_sq(0), st)
+    synthdata.fill_gpu(md.ptr("grad", 0), n, w.spec_grad(0, 1), st)
+    ws = B.Workspace(1)
+    hp = B.hparams()
+    gn, gf = run_gpu(md, ws, B.AH_BF16, 1, hp)
+
+    def window(spec_fn, lo, cnt, dt, *a):
+        spec = spec_fn(0, *a)
+        spec.first_index = lo
+        return synthdata.fill_cpu(np.empty(cnt, dt), spec)
+
+    piece = 1 << 26
+    starts = list(range(0, n, piece))
+
+    def part(lo):
+        g = window(w.spec_grad, lo, min(piece, n - lo), np.uint16, 1)
+        return oracle.grad_accumulate(g, oracle.BF16, 1.0)
+
+    with cf.ThreadPoolExecutor(N_THREADS) as ex:
+        parts = list(ex.map(part, starts))
+    on, of = oracle.grad_finish(sum(p[0] for p in parts), max(p[1] for p in parts))
+    assert gf == of == 0 and abs(gn - on) <= 1e-5 * on
+    cnt = 1 << 16
+    for lo in (0, (1 << 32) - cnt // 2, n - cnt + 8, n - 1000):
+        k = min(cnt, n - lo)
+        ref = dict(grad=window(w.spec_grad, lo, k, np.uint16, 1), param_lp=window(w.spec_param_lp, lo, k, np.uint16),
+                   master=window(w.spec_master, lo, k, np.float32), exp_avg=window(w.spec_exp_avg, lo, k, np.float32),
+                   exp_avg_sq=window(w.spec_exp_avg_sq, lo, k, np.float32))
+        old = dict(master=ref["master"].copy(), exp_avg=ref["exp_avg"].copy(), exp_avg_sq=ref["exp_avg_sq"].copy())
+        oracle.adamw_chunk(ref["grad"], ref["param_lp"], ref["master"], ref["exp_avg"], ref["exp_avg_sq"], oracle.BF16,
+                           1, oracle_hp(hp), on, 0)
+        got = {}
+        for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):
+            a = md.view(s, 0)[lo:lo + k].cpu().numpy()
+            got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
+        compare_state(got, ref, "huge chunk window at %d" % lo, old)
+    ws.close()
