@@ -540,3 +540,43 @@ def test_single_chunk_beyond_2_to_32_elements():
             got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
         compare_state(got, ref, "huge chunk window at %d" % lo, old)
     ws.close()
+
+
+def _random_hparams(rng):
+    pick = lambda xs: xs[int(rng.integers(0, len(xs)))]
+    return dict(lr=float(pick([1e-5, 1e-4, 3e-3, 0.1, 0.0])), beta1=float(pick([0.0, 0.5, 0.9, 0.99])),
+                beta2=float(pick([0.0, 0.9, 0.999, 0.9999])), eps=float(pick([1e-12, 1e-8, 1e-6, 1e-3])),
+                weight_decay=float(pick([0.0, 0.01, 0.1, 1.0])), max_grad_norm=float(pick([0.0, -1.0, 1e-3, 0.05, 1.0, 1e6])),
+                loss_scale=float(pick([1.0, 3.0, 1000.0, 65536.0, 0.125])))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_hyperparameters_and_steps(seed):
+    """Parity over the hyper-parameter space: zero betas, no decay, no clipping / heavy clipping,
+    loss scales that are not powers of two (both sides multiply by the fp64 reciprocal), large t."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = B.AH_BF16 if seed % 2 == 0 else B.AH_FP16
+    kw = _random_hparams(rng)
+    if dtype == B.AH_FP16 and kw["loss_scale"] > 1000.0:
+        kw["loss_scale"] = 1000.0                      # keep scaled fp16 gradients finite
+    hp, ohp = B.hparams(**kw), oracle.hparams(**kw)
+    numels = [int(x) for x in rng.integers(1, 30_000, 5)]
+    states = [random_state(n, dtype, rng, scale=kw["loss_scale"]) for n in numels]
+    md = ModelData(numels)
+    for i, st in enumerate(states):
+        upload(md, i, st)
+    ws = B.Workspace(len(numels))
+    extra = float(rng.choice([0.0, 1e-6, 3.5]))
+    for step in (int(rng.integers(1, 5)), int(rng.integers(5, 100_000))):
+        arr = md.chunk_array()
+        gn, gf = ws.autohete_grad_prep(arr, len(numels), dtype, kw["loss_scale"], extra, stream_handle(), want_result=True)
+        ws.autohete_adamw_step(arr, len(numels), dtype, step, hp, stream_handle())
+        torch.cuda.synchronize()
+        for st in states:
+            st["old"] = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(), exp_avg_sq=st["exp_avg_sq"].copy())
+        on, of = oracle.full_step(states, dtype, step, ohp, extra)
+        check_norm(gn, gf, on, of)
+        for i, st in enumerate(states):
+            compare_state(download(md, i), st, "seed=%d %r step=%d chunk=%d" % (seed, kw, step, i), st["old"],
+                          drift_steps=1)
+    ws.close()

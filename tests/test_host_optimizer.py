@@ -122,3 +122,24 @@ def test_host_errors():
     assert lib.autohete_host_adamw_step(arr, 1, B.AH_BF16, 1, ctypes.byref(bad), 1.0, 0, 1) == B.AH_EINVAL
     nul = B.chunk_array([(st["grad"].ctypes.data, None, None, st["exp_avg"].ctypes.data, st["exp_avg_sq"].ctypes.data, 64)])
     assert lib.autohete_host_adamw_step(nul, 1, B.AH_BF16, 1, ctypes.byref(hp), 1.0, 0, 1) == B.AH_EINVAL
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_host_random_hyperparameters_bit_identical(seed):
+    rng = np.random.default_rng(500 + seed)
+    pick = lambda xs: xs[int(rng.integers(0, len(xs)))]
+    dtype = B.AH_BF16 if seed % 2 == 0 else B.AH_FP16
+    kw = dict(lr=float(pick([1e-5, 1e-4, 3e-3, 0.1, 0.0])), beta1=float(pick([0.0, 0.5, 0.9, 0.99])),
+              beta2=float(pick([0.0, 0.9, 0.999, 0.9999])), eps=float(pick([1e-12, 1e-8, 1e-6, 1e-3])),
+              weight_decay=float(pick([0.0, 0.01, 0.1, 1.0])), max_grad_norm=float(pick([0.0, -1.0, 1e-3, 0.05, 1.0, 1e6])),
+              loss_scale=float(pick([1.0, 3.0, 1000.0, 0.125])))
+    n = int(rng.integers(1, 50_000))
+    a = make_state(n, dtype, kw["loss_scale"])
+    b = {k: v.copy() for k, v in a.items()}
+    step = int(rng.integers(1, 100_000))
+    sumsq = float(rng.choice([0.0, 1e-9, 0.37, 1e4]))
+    B.autohete_host_adamw_step(host_chunks([a]), 1, dtype, step, B.hparams(**kw), sumsq, 0, 4)
+    oracle.adamw_chunk(b["grad"], b["param_lp"], b["master"], b["exp_avg"], b["exp_avg_sq"], dtype, step,
+                       oracle.hparams(**kw), float(np.sqrt(sumsq)), 0)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes(), (kw, step, k)
