@@ -7,7 +7,8 @@ autohete_grad_prep (unscale + finite check + global L2 norm) followed by autohet
 GPU-resident chunk of the workload.  All inputs -- the model data and one gradient slab per
 step -- are generated on the device and resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see README for the fields).  The CPU oracle is timed on a
+Prints ONE JSON line: metric/value (parameters per second), ms_per_step, the whole-step HBM figure, a
+`roofline` object for the dominant kernel, the prep kernel's figures and `cpu_baseline`.  The CPU oracle is timed on a
 bounded sample of the same workload as a reported baseline only.
 """
 import argparse

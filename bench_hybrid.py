@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Hybrid placement end to end: the GPU half and the host half of one optimizer step.
 
-Workload gpt-13b-half-resident (benchmark configs[3]): the first half of the chunks keeps its
+Workload gpt-13b-half-resident (the 13B-parameter configuration with half of the chunks resident): the first half of the chunks keeps its
 optimizer states in HBM, the second half keeps fp32 master / momentum / variance in host memory.
 One step = global gradient norm on the GPU, the GPU update of the resident chunks, and for every
 host-owned chunk: 16-bit gradients D2H, host AdamW (libautohete's AVX-512 path), 16-bit parameters

@@ -162,8 +162,9 @@ class Run:
         mism = {k: sum(s[k] for s in self.stats) for k in ("master_mismatch", "exp_avg_mismatch",
                                                             "exp_avg_sq_mismatch", "param_lp_mismatch",
                                                             "master_relaxed", "exp_avg_relaxed", "exp_avg_sq_relaxed")}
-        os.makedirs("gpurun_out", exist_ok=True)
-        with open("gpurun_out/parity_%s%s.txt" % (w.name, "_split" if self.split else ""), "w") as fh:
+        out_dir = os.environ.get("AUTOHETE_PARITY_REPORT_DIR", "parity_reports")
+        os.makedirs(out_dir, exist_ok=True)
+        with open(os.path.join(out_dir, "parity_%s%s.txt" % (w.name, "_split" if self.split else "")), "w") as fh:
             fh.write("workload %s: %d iterations, %d updates, sampled chunks %s (free-running: %s)\n" %
                      (w.name, self.done, self.t - 1, self.sample, self.free))
             fh.write("element-steps compared: %d\nworst error vs oracle (ulp, cancelled elements aside): %s\n"
