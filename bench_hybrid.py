@@ -1,13 +1,13 @@
 #!/usr/bin/env python3
 """Hybrid placement end to end: the GPU half and the host half of one optimizer step.
 
-Workload gpt-13b-half-resident (the 13B-parameter configuration with half of the chunks resident): the first half of the chunks keeps its
-optimizer states in HBM, the second half keeps fp32 master / momentum / variance in host memory.
+Workload gpt-13b-half-resident (13B parameters, half of the chunks resident): the first half of the
+chunks keeps its optimizer states in HBM, the second half keeps fp32 master / momentum / variance in host memory.
 One step = global gradient norm on the GPU, the GPU update of the resident chunks, and for every
 host-owned chunk: 16-bit gradients D2H, host AdamW (libautohete's AVX-512 path), 16-bit parameters
 H2D, pipelined chunk by chunk (paper_2503_01890_amd/hybrid.py).  Reports the quantities the
 paper's cost model takes as inputs: t_optim^gpu, t_optim^cpu, t_d2h, t_h2d (per parameter and per
-201 M-parameter block), and the end-to-end step time.  Prints one JSON line.  Synthetic inputs.
+transformer block), and the end-to-end step time.  Prints one JSON line.  Synthetic inputs.
 """
 import argparse
 import concurrent.futures as cf

@@ -580,3 +580,59 @@ def test_random_hyperparameters_and_steps(seed):
             compare_state(download(md, i), st, "seed=%d %r step=%d chunk=%d" % (seed, kw, step, i), st["old"],
                           drift_steps=1)
     ws.close()
+
+
+def test_seventy_thousand_tiny_chunks_cross_the_grid_row_limit():
+    """More chunks than one launch has grid rows (65535): the launcher must split the group."""
+    rng = np.random.default_rng(8)
+    n_chunks = 70_000
+    numels = [int(x) for x in rng.integers(1, 40, n_chunks)]
+    total = sum(numels)
+    flat = random_state(total, B.AH_BF16, rng)
+    md = ModelData(numels)
+    # upload through the slabs directly: chunk i sits at md.offset[i]
+    idx = np.concatenate([np.arange(o, o + n) for o, n in zip(md.offset, numels)])
+    for s in STREAMS:
+        a = flat[s]
+        slab = md.slab[s]
+        slab.zero_()
+        slab[torch.from_numpy(idx).to(slab.device)] = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(slab.device)
+    ws = B.Workspace(n_chunks)
+    hp = B.hparams(max_grad_norm=0.01)
+    gn, gf = run_gpu(md, ws, B.AH_BF16, 3, hp)
+    old = dict(master=flat["master"].copy(), exp_avg=flat["exp_avg"].copy(), exp_avg_sq=flat["exp_avg_sq"].copy())
+    on, of = oracle.full_step([flat], oracle.BF16, 3, oracle_hp(hp))
+    check_norm(gn, gf, on, of)
+    got = {}
+    dev_idx = torch.from_numpy(idx).to(md.slab["master"].device)
+    for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):
+        a = md.slab[s][dev_idx].cpu().numpy()
+        got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
+    compare_state(got, flat, "70k chunks", old)
+    ws.close()
+
+
+def test_two_workspaces_on_two_streams_do_not_interfere():
+    rng = np.random.default_rng(9)
+    numels = [300_000, 123_457]
+    sets = []
+    for k in range(2):
+        states = [random_state(n, B.AH_BF16, rng) for n in numels]
+        md = ModelData(numels)
+        for i, st in enumerate(states):
+            upload(md, i, st)
+        sets.append((states, md, B.Workspace(2), torch.cuda.Stream(), B.hparams(max_grad_norm=0.03 * (k + 1))))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for states, md, ws, stream, hp in sets:           # interleave the launches of the two streams
+            with torch.cuda.stream(stream):
+                arr = md.chunk_array()
+                ws.autohete_grad_prep(arr, 2, B.AH_BF16, 1.0, 0.0, stream.cuda_stream)
+                ws.autohete_adamw_step(arr, 2, B.AH_BF16, rep + 1, hp, stream.cuda_stream)
+    torch.cuda.synchronize()
+    for states, md, ws, stream, hp in sets:
+        for rep in range(3):
+            run_oracle(states, oracle.BF16, rep + 1, hp)
+        for i, st in enumerate(states):
+            compare_state(download(md, i), st, "two streams", st["old"], drift_steps=3)
+        ws.close()
