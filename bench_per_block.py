@@ -11,6 +11,9 @@ path (Eq. 5, first arm).  This script measures, for one workload on one MI355X:
                 the NEXT iteration's norm and one autohete_adamw_step that clips with the
                 PREVIOUS iteration's norm (a global norm cannot be known before the last block's
                 gradients exist); two workspaces alternate
+  per_block_carry  the same schedule through autohete_adamw_step_carry: one launch per partition
+                updates it and gathers its squares for the next norm, reading the gradients once
+                (28 B/element instead of 30)
   compute       a synthetic backward pass: bf16 GEMMs per block on the compute stream
   overlapped    compute on one stream, per-block optimizer work on a second stream of the same
                 (default) priority, block i's optimizer work released by an event after block i's
@@ -90,15 +93,21 @@ def main():
         nxt.autohete_grad_prep_accumulate(arr, k, w.dtype, w.loss_scale, stream_handle)
         cur.autohete_adamw_step(arr, k, w.dtype, step[0], hp, stream_handle)
 
-    def per_block(stream_handle=None, events=None):
+    def per_block(stream_handle=None, events=None, carry=False):
         s = st if stream_handle is None else stream_handle
         cur, nxt = ws[step[0] % 2], ws[(step[0] + 1) % 2]
         nxt.autohete_grad_result_set(0.0, 0, s)
         for i in range(len(parts)):
             if events is not None:
                 side.wait_event(events[i])
-            optimizer_block(i, cur, nxt, s)
+            if carry:
+                cur.autohete_adamw_step_carry(nxt, parts[i][0], parts[i][1], w.dtype, step[0], hp, s)
+            else:
+                optimizer_block(i, cur, nxt, s)
         step[0] += 1
+
+    def per_block_carry():
+        per_block(carry=True)
 
     def compute(events=None):
         for i in range(len(parts)):
@@ -107,12 +116,15 @@ def main():
             if events is not None:
                 events[i].record(main_stream)
 
-    def overlapped():
+    def overlapped(carry=False):
         events = [torch.cuda.Event() for _ in parts]
         compute(events)
         with torch.cuda.stream(side):
-            per_block(side.cuda_stream, events)
+            per_block(side.cuda_stream, events, carry)
         main_stream.wait_stream(side)
+
+    def overlapped_carry():
+        overlapped(True)
 
     def timed(fn):
         fn()
@@ -132,12 +144,15 @@ def main():
            "blocks_per_cu": args.blocks_per_cu or "default"}
     res["one_shot_ms"] = timed(one_shot)
     res["per_block_ms"] = timed(per_block)
+    res["per_block_carry_ms"] = timed(per_block_carry)
     res["compute_ms"] = timed(compute)
     res["overlapped_ms"] = timed(overlapped)
+    res["overlapped_carry_ms"] = timed(overlapped_carry)
     res["serial_sum_ms"] = res["per_block_ms"] + res["compute_ms"]
     res["ideal_overlap_ms"] = max(res["per_block_ms"], res["compute_ms"])
     res["per_block_GBps"] = 30 * n * C / res["per_block_ms"] / 1e6
     res["one_shot_GBps"] = 30 * n * C / res["one_shot_ms"] / 1e6
+    res["per_block_carry_GBps"] = 28 * n * C / res["per_block_carry_ms"] / 1e6
     for x in ws:
         x.close()
     print(json.dumps(res))

@@ -165,6 +165,34 @@ int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t
                          int lowp_dtype, void *stream);
 
 /*
+ * autohete_adamw_step that also carries the gradient norm forward.  When each block's optimizer
+ * is stepped as soon as that block's gradients exist (section 3.2.2, footnote to Eq. 5), the
+ * update of an early block cannot wait for a norm over gradients the backward pass has not
+ * produced yet: it clips with the norm the workspace `ws` already holds (the previous
+ * iteration's, or one set by autohete_grad_result_set), and the squares of the gradients it
+ * reads anyway are summed for the next one.  The call leaves every stream and both workspaces
+ * exactly as
+ *     autohete_grad_prep_accumulate(ws_next, chunks, n_chunks, lowp_dtype, hp->loss_scale, stream);
+ *     autohete_adamw_step(ws, chunks, n_chunks, lowp_dtype, step, hp, stream);
+ * would, up to the order of the fp64 additions inside ws_next's S, while reading the gradients
+ * once: 28 bytes per element instead of 30.  The sum is bit-reproducible for a given chunk list
+ * and tuning.  If ws holds a skip flag nothing is updated but the squares are still gathered.
+ * Note what any such schedule implies: a non-finite gradient is only seen in ws_next, after the
+ * blocks stepped earlier in the same iteration have been written.
+ *   ws_next   must differ from ws and live on the same device; its result is accumulated into,
+ *             so start an iteration with autohete_grad_result_set(ws_next, 0, 0, stream)
+ * The squares are kept as one fp64 partial per wavefront in a buffer of ws_next (numel / 32 bytes
+ * per iteration with the default tuning) and are summed into ws_next's result, by one small
+ * kernel, on the stream of the next call that uses or reads that result -- which the caller has
+ * to order after these updates anyway.  The buffer grows by doubling until it holds a whole
+ * iteration; growing allocates and thereby waits for the device (first iteration only).
+ * Errors: as autohete_adamw_step; AH_EINVAL also if ws_next is NULL or equals ws.
+ */
+int autohete_adamw_step_carry(autohete_ws *ws, autohete_ws *ws_next, const autohete_chunk *chunks,
+                              uint64_t n_chunks, int lowp_dtype, uint64_t step,
+                              const autohete_hparams *hp, void *stream);
+
+/*
  * Read (waits for the stream) or overwrite (enqueued on the stream) the workspace's
  * gradient result.  Setting it lets a caller step a block with a norm obtained elsewhere
  * -- e.g. per-block stepping during backward with clipping off (sumsq = 0), or with the

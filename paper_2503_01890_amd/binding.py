@@ -83,6 +83,10 @@ _lib.autohete_grad_prep_accumulate.argtypes = [ctypes.c_void_p, ctypes.POINTER(a
 _lib.autohete_adamw_step.restype = ctypes.c_int
 _lib.autohete_adamw_step.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.POINTER(autohete_hparams), ctypes.c_void_p]
+_lib.autohete_adamw_step_carry.restype = ctypes.c_int
+_lib.autohete_adamw_step_carry.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(autohete_chunk),
+                                           ctypes.c_uint64, ctypes.c_int, ctypes.c_uint64,
+                                           ctypes.POINTER(autohete_hparams), ctypes.c_void_p]
 _lib.autohete_adamw_step_master.restype = ctypes.c_int
 _lib.autohete_adamw_step_master.argtypes = _lib.autohete_adamw_step.argtypes
 _lib.autohete_cast_params.restype = ctypes.c_int
@@ -205,6 +209,11 @@ class Workspace:
     def autohete_adamw_step(self, chunks, n_chunks, lowp_dtype, step, hp, stream=0):
         _check(_lib.autohete_adamw_step(self._h, chunks, n_chunks, lowp_dtype, int(step), ctypes.byref(hp),
                                         ctypes.c_void_p(stream)), "autohete_adamw_step")
+
+    def autohete_adamw_step_carry(self, ws_next, chunks, n_chunks, lowp_dtype, step, hp, stream=0):
+        _check(_lib.autohete_adamw_step_carry(self._h, ws_next._h if ws_next is not None else None, chunks,
+                                              n_chunks, lowp_dtype, int(step), ctypes.byref(hp),
+                                              ctypes.c_void_p(stream)), "autohete_adamw_step_carry")
 
     def autohete_adamw_step_master(self, chunks, n_chunks, lowp_dtype, step, hp, stream=0):
         _check(_lib.autohete_adamw_step_master(self._h, chunks, n_chunks, lowp_dtype, int(step), ctypes.byref(hp),

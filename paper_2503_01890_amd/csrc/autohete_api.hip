@@ -42,6 +42,14 @@ struct autohete_ws {
     /* launch groups of the current step table: rows [first, first+rows) share grid_x */
     struct Group { uint32_t first, rows; uint64_t max_tiles; };
     std::vector<Group> step_groups;
+    uint64_t step_tiles = 0;                    /* tiles of the current step table, all groups */
+    /* Norm carried INTO this workspace by autohete_adamw_step_carry calls: one fp64 slot per
+     * wavefront of those calls, appended call after call and summed into d_res by one fold kernel
+     * when the result is next needed.  Grown on demand, never shrunk. */
+    double *d_wave_partials = nullptr;
+    uint64_t wave_partials_cap = 0;
+    uint64_t carried_slots = 0;                 /* written (or enqueued) but not folded yet */
+    double carried_inv_scale = 1.0;             /* 1 / loss_scale of those slots */
 };
 
 namespace {
@@ -50,6 +58,7 @@ namespace {
  * Default: 4 elements per lane, one wavefront per block, Newton fp64, at most 10 blocks per CU. */
 constexpr int64_t kDefaultVariant = 4 | (0 << 4) | (1 << 8);
 constexpr int kDefaultBlocksPerCu = 10;
+constexpr int kDefaultCarryBlocksPerCu = 11; /* its waves live a little longer: 10 -> 28.9, 11 -> 28.5, 14 -> 29.0 ms */
 constexpr int kDefaultCastBlocksPerCu = 24; /* measured: 64 -> 6.38, 24 -> 6.88, 16 -> 6.10 TB/s */
 
 bool decode_variant(int64_t v, ah::StepVariant *out)
@@ -168,7 +177,13 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
         fill_row(tab[r], chunks[i], 0);
         row_tiles[r] = tiles[i];
     }
+    uint64_t tile_run = 0; /* rows number their tiles consecutively in table order */
+    for (uint64_t r = 0; r < n; ++r) {
+        tab[r].tile_begin = tile_run;
+        tile_run += row_tiles[r];
+    }
     memset(&tab[n], 0, sizeof(DevChunk));
+    tab[n].tile_begin = tile_run;
     std::vector<autohete_ws::Group> groups;
     for (int b = 0; b < 65; ++b) {
         for (uint32_t first = start[b]; first < start[b] + count[b]; first += 65535u) {
@@ -182,6 +197,7 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
     int rc = upload_table(ws, 1, tab, stream, &changed);
     if (rc != AH_OK) return rc;
     ws->step_groups.swap(groups);
+    ws->step_tiles = tile_run;
     return AH_OK;
 }
 
@@ -209,6 +225,49 @@ struct DeviceGuard { /* run on the workspace's device, restore the caller's afte
         if (ok && prev >= 0) (void)hipSetDevice(prev);
     }
 };
+
+/* Fold the carried slots into the workspace's result, on `stream` (which the caller has ordered
+ * after the kernels that wrote them, as for any use of the result). */
+int flush_carried(autohete_ws *ws, hipStream_t stream)
+{
+    if (!ws->carried_slots) return AH_OK;
+    const uint64_t per_block = (uint64_t)ah::kThreads * 16;
+    const uint64_t blocks = std::min<uint64_t>((uint64_t)ws->n_cu, (ws->carried_slots + per_block - 1) / per_block);
+    const uint64_t n = ws->carried_slots;
+    ws->carried_slots = 0;
+    return ah::launch_fold((unsigned)blocks, stream, ws->d_wave_partials, n, ws->carried_inv_scale, ws->d_partials,
+                           ws->d_ticket, ws->d_res) == hipSuccess
+               ? AH_OK : AH_EHIP;
+}
+
+/* Room for `slots` more carried slots with the given scale; returns the index of the first.
+ * When the buffer is full the pending slots are folded first; it then at least doubles, so that
+ * after a few calls a whole iteration of per-block calls is folded by a single launch.  Growing
+ * frees the old buffer, which waits for the device. */
+int reserve_carried(autohete_ws *ws, uint64_t slots, double inv_scale, hipStream_t stream, uint64_t *base)
+{
+    if (ws->carried_slots && ws->carried_inv_scale != inv_scale) {
+        int rc = flush_carried(ws, stream);
+        if (rc != AH_OK) return rc;
+    }
+    if (ws->carried_slots + slots > ws->wave_partials_cap) {
+        const uint64_t want = std::max(ws->carried_slots + slots, 2 * ws->wave_partials_cap);
+        int rc = flush_carried(ws, stream);
+        if (rc != AH_OK) return rc;
+        if (ws->d_wave_partials) (void)hipFree(ws->d_wave_partials);
+        ws->d_wave_partials = nullptr;
+        ws->wave_partials_cap = 0;
+        if (hipMalloc(&ws->d_wave_partials, want * sizeof(double)) != hipSuccess) {
+            (void)hipGetLastError();
+            return AH_ENOMEM;
+        }
+        ws->wave_partials_cap = want;
+    }
+    *base = ws->carried_slots;
+    ws->carried_slots += slots;
+    ws->carried_inv_scale = inv_scale;
+    return AH_OK;
+}
 
 }  // namespace
 
@@ -302,6 +361,7 @@ int autohete_ws_destroy(autohete_ws *ws)
         }
     }
     if (ws->d_partials) (void)hipFree(ws->d_partials);
+    if (ws->d_wave_partials) (void)hipFree(ws->d_wave_partials);
     if (ws->d_ticket) (void)hipFree(ws->d_ticket);
     if (ws->d_res) (void)hipFree(ws->d_res);
     if (ws->h_res) (void)hipHostFree(ws->h_res);
@@ -357,6 +417,11 @@ static int prep_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     uint64_t tiles = 0;
     int rc;
+    if (accumulate) {
+        if ((rc = flush_carried(ws, stream)) != AH_OK) return rc;
+    } else {
+        ws->carried_slots = 0; /* the result is replaced: a carried sum not folded yet goes with it */
+    }
     try {
         rc = build_prep_table(ws, chunks, n_chunks, ah::prep_tile_elems(), stream, &tiles);
     } catch (...) { /* std::bad_alloc from the host-side table: nothing may be thrown across the C ABI */
@@ -391,10 +456,14 @@ int autohete_grad_prep_accumulate(autohete_ws *ws, const autohete_chunk *chunks,
     return prep_common(ws, chunks, n_chunks, lowp_dtype, loss_scale, 0.0, true, stream, nullptr, nullptr);
 }
 
+/* carry_to != NULL: the norm-carrying update; the squares of these chunks' gradients are folded
+ * into carry_to's result. */
 static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
-                       uint64_t step, const autohete_hparams *hp, void *stream_, bool write_back)
+                       uint64_t step, const autohete_hparams *hp, void *stream_, bool write_back,
+                       autohete_ws *carry_to = nullptr)
 {
     if (!ws || !hp || step == 0 || (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16)) return AH_EINVAL;
+    if (carry_to && (carry_to == ws || carry_to->device != ws->device)) return AH_EINVAL;
     auto nonneg = [](float x) { return isfinite(x) && x >= 0.0f; };
     if (!nonneg(hp->lr) || !nonneg(hp->eps) || !nonneg(hp->weight_decay) || !isfinite(hp->max_grad_norm) ||
         !(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) ||
@@ -415,6 +484,7 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     }
     if (rc != AH_OK) return rc;
     if (n_chunks == 0) return AH_OK;
+    if ((rc = flush_carried(ws, stream)) != AH_OK) return rc; /* the result this update clips with */
 
     /* Per-launch constants, fp64 from the fp32 hyper-parameters. */
     ah::StepConsts k;
@@ -433,10 +503,23 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     k.wd = (double)hp->weight_decay;
 
     const unsigned lds = lds_for_cap(ws, ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu
-                                                                      : kDefaultBlocksPerCu);
+                                         : carry_to ? kDefaultCarryBlocksPerCu : kDefaultBlocksPerCu);
+    if (!carry_to) {
+        for (const autohete_ws::Group &grp : ws->step_groups) {
+            if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
+                                ws->d_tab[1] + grp.first, ws->d_res, k) != hipSuccess)
+                return AH_EHIP;
+        }
+        return AH_OK;
+    }
+    /* One slot per wavefront, appended to what earlier calls carried into the same workspace. */
+    uint64_t base = 0;
+    rc = reserve_carried(carry_to, ws->step_tiles * (uint64_t)(var.block / 64), k.inv_scale, stream, &base);
+    if (rc != AH_OK) return rc;
     for (const autohete_ws::Group &grp : ws->step_groups) {
-        if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
-                            ws->d_tab[1] + grp.first, ws->d_res, k) != hipSuccess)
+        if (ah::launch_step_carry(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
+                                  ws->d_tab[1] + grp.first, ws->d_res, k, carry_to->d_wave_partials, base) !=
+            hipSuccess)
             return AH_EHIP;
     }
     return AH_OK;
@@ -446,6 +529,14 @@ int autohete_adamw_step(autohete_ws *ws, const autohete_chunk *chunks, uint64_t 
                         uint64_t step, const autohete_hparams *hp, void *stream)
 {
     return step_common(ws, chunks, n_chunks, lowp_dtype, step, hp, stream, true);
+}
+
+int autohete_adamw_step_carry(autohete_ws *ws, autohete_ws *ws_next, const autohete_chunk *chunks,
+                              uint64_t n_chunks, int lowp_dtype, uint64_t step, const autohete_hparams *hp,
+                              void *stream)
+{
+    if (!ws_next) return AH_EINVAL;
+    return step_common(ws, chunks, n_chunks, lowp_dtype, step, hp, stream, true, ws_next);
 }
 
 int autohete_adamw_step_master(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype,
@@ -483,6 +574,8 @@ int autohete_grad_result_get(autohete_ws *ws, void *stream, double *sumsq, float
     if (!ws) return AH_EINVAL;
     DeviceGuard g(ws->device);
     if (!g.ok) return AH_EHIP;
+    int rc = flush_carried(ws, static_cast<hipStream_t>(stream));
+    if (rc != AH_OK) return rc;
     return read_result(ws, static_cast<hipStream_t>(stream), sumsq, norm, found_inf);
 }
 
@@ -491,6 +584,7 @@ int autohete_grad_result_set(autohete_ws *ws, double sumsq, uint32_t found_inf, 
     if (!ws) return AH_EINVAL;
     DeviceGuard g(ws->device);
     if (!g.ok) return AH_EHIP;
+    ws->carried_slots = 0; /* overwritten with the rest of the result */
     return ah::launch_set_result(static_cast<hipStream_t>(stream), ws->d_res, sumsq, found_inf) == hipSuccess
                ? AH_OK : AH_EHIP;
 }

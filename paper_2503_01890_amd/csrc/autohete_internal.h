@@ -52,6 +52,14 @@ bool step_variant_valid(StepVariant s);
  * per block caps the blocks resident per CU. */
 hipError_t launch_step(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
                        hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k);
+/* The same launch shape for the norm-carrying update: wave w of block (x, y) writes slot
+ * slot_base + (tab[y].tile_begin + x) * (block / 64) + w of wave_partials; launch_fold sums n
+ * slots into res (S += sum * inv_scale^2). */
+hipError_t launch_step_carry(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
+                             hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k,
+                             double *wave_partials, uint64_t slot_base);
+hipError_t launch_fold(unsigned blocks, hipStream_t stream, const double *wave_partials, uint64_t n,
+                       double inv_scale, double *partials, uint32_t *ticket, GradResult *res);
 /* master -> 16-bit conversion: grid_x tiles of 512 elements for each of grid_y table rows */
 constexpr uint32_t kCastTileElems = 512;
 hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, unsigned lds_bytes, hipStream_t stream,

@@ -261,6 +261,106 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
     }
 }
 
+/* Sum of x over the 64 lanes of a wavefront, returned in every lane, in a fixed order and
+ * without LDS traffic: four butterfly steps inside each row of 16 lanes through DPP lane
+ * permutations (neighbour, pair, mirrored half-row, mirrored row), then the four row sums are
+ * read as scalars and added in row order. */
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double lane_value(double x, int lane)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double wave_sum(double x)
+{
+    x += dpp_move<0xB1>(x);  /* quad_perm [1,0,3,2]: lane ^ 1 */
+    x += dpp_move<0x4E>(x);  /* quad_perm [2,3,0,1]: lane ^ 2 */
+    x += dpp_move<0x141>(x); /* row_half_mirror: the other quad of the 8 */
+    x += dpp_move<0x140>(x); /* row_mirror: the other half of the 16 */
+    return ((lane_value(x, 0) + lane_value(x, 16)) + lane_value(x, 32)) + lane_value(x, 48);
+}
+
+/*
+ * The update kernel that also carries the gradient norm forward: the same update, clipped with
+ * the norm in `res` (gathered earlier), while the squares of the gradients it reads anyway are
+ * summed for the NEXT norm -- 28 B/element where grad_prep + adamw_step move 30.  Used when
+ * blocks are stepped as their gradients appear (paper section 3.2.2, footnote to Eq. 5), where a
+ * block's update cannot wait for the norm over gradients that do not exist yet.
+ * Every wavefront leaves one fp64 partial at a slot fixed by its position in the launch:
+ * slot = slot_base + (tile_begin of the row + blockIdx.x) * waves per block + wave.
+ * fold_partials_kernel later sums the slots in a fixed order, so the sum is reproducible.  On
+ * skip (res->found_inf) the streams are left alone but the squares are still gathered.
+ */
+template <int DT, int VEC, int BS, int MODE>
+__global__ void __launch_bounds__(BS)
+adamw_step_carry_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k,
+                        double *__restrict__ wave_partials, uint64_t slot_base)
+{
+    const GradResult r = *res;
+    const DevChunk ch = tab[blockIdx.y];
+    const uint64_t tile0 = (uint64_t)blockIdx.x * (BS * VEC);
+    /* A whole block beyond the chunk owns no slot and leaves.  The flag (0 or 1) takes part in the
+     * test only so that the result is fetched together with the table row, ahead of the branch,
+     * as in adamw_step_kernel: one dependent scalar round trip fewer before the vector loads. */
+    if ((uint32_t)(tile0 >= ch.numel) | (r.found_inf >> 1)) return;
+    const uint64_t off = tile0 + threadIdx.x * VEC;
+    typedef typename VecTypes<VEC>::f32 fvec;
+    typedef typename VecTypes<VEC>::lowp hvec;
+    double sq = 0.0;
+    if (!r.found_inf && off + VEC <= ch.numel) {
+        const hvec graw = ld<true>(gptr<hvec>(ch.grad + off));
+        const fvec pv = ld<true>(gptr<fvec>((const float *)ch.master + off));
+        const fvec mv = ld<true>(gptr<fvec>((const float *)ch.exp_avg + off));
+        const fvec vv = ld<true>(gptr<fvec>((const float *)ch.exp_avg_sq + off));
+        __builtin_amdgcn_sched_barrier(0);
+        const double coef = clip_coef(k.max_norm, r.norm_d);
+        float gf[VEC], pp[VEC], mm[VEC], vs[VEC];
+        unpack_lowp<DT, VEC>(graw, gf);
+        split<VEC>(pv, pp);
+        split<VEC>(mv, mm);
+        split<VEC>(vv, vs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            sq += (double)gf[j] * (double)gf[j];
+            adamw_elem<MODE>(gf[j], pp[j], mm[j], vs[j], k, coef);
+        }
+        st_stream(gptr<fvec>(ch.master + off), join<VEC>(pp));
+        st_stream(gptr<fvec>(ch.exp_avg + off), join<VEC>(mm));
+        st_stream(gptr<fvec>(ch.exp_avg_sq + off), join<VEC>(vs));
+        st_stream(gptr<hvec>(ch.param_lp + off), pack_lowp<DT, VEC>(pp));
+    } else if (off < ch.numel) {
+        /* element by element: the ragged end of a chunk, and every lane of a skipped step (which
+         * only gathers squares; kept apart from the path above so that its gradient load is not
+         * merged with that one and waited for ahead of the other three) */
+        const double coef = clip_coef(k.max_norm, r.norm_d);
+        const uint64_t end = off + VEC < ch.numel ? off + VEC : ch.numel;
+        for (uint64_t i = off; i < end; ++i) {
+            const float g = lowp_to_f32<DT>(gptr<uint16_t>(ch.grad)[i]);
+            sq += (double)g * (double)g;
+            if (r.found_inf) continue;
+            float p = gptr<float>(ch.master)[i], m = gptr<float>(ch.exp_avg)[i], v = gptr<float>(ch.exp_avg_sq)[i];
+            adamw_elem<MODE>(g, p, m, v, k, coef);
+            gptr<float>(ch.master)[i] = p;
+            gptr<float>(ch.exp_avg)[i] = m;
+            gptr<float>(ch.exp_avg_sq)[i] = v;
+            gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(p);
+        }
+    }
+    /* all 64 lanes of every wave of the block arrive here (lanes beyond the chunk carry 0) */
+    sq = wave_sum(sq);
+    if ((threadIdx.x & 63) == 0)
+        wave_partials[slot_base + (ch.tile_begin + blockIdx.x) * (BS / 64) + (threadIdx.x >> 6)] = sq;
+}
+
 /*
  * On-demand materialisation of the 16-bit parameters from the fp32 master copy (paper section
  * 3.2.2, footnote: blocks whose optimizer states stay on the GPU keep no 16-bit parameters; they
@@ -303,6 +403,26 @@ __device__ __forceinline__ double block_sum(double x, double *lds4)
     const double s = ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
     __syncthreads();
     return s;
+}
+
+/* Final scalar step of a norm pass (one thread): S = raw_sum / loss_scale^2 + extra, folded into
+ * the result already there when `accumulate` (gradient norm gathered block by block while the
+ * backward pass still runs); a non-finite S or a carried flag means skip. */
+__device__ __forceinline__ void publish_total(GradResult *res, double raw_sum, double inv_scale, double extra_sumsq,
+                                              uint32_t accumulate)
+{
+    double total = raw_sum * inv_scale * inv_scale + extra_sumsq;
+    bool carried_flag = false;
+    if (accumulate) {
+        total += res->sumsq;
+        carried_flag = res->found_inf != 0;
+    }
+    const bool bad = carried_flag || !__builtin_isfinite(total);
+    const double nd = bad ? __builtin_nan("") : sqrt(total);
+    res->sumsq = total;
+    res->norm_d = nd;
+    res->norm = (float)nd;
+    res->found_inf = bad ? 1u : 0u;
 }
 
 template <int DT>
@@ -375,23 +495,52 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
         s += __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s = block_sum(s, lds4);
     if (threadIdx.x == 0) {
-        /* accumulate: fold this call into the result already in the workspace (gradient norm
-         * gathered block by block while the backward pass still runs) */
-        double total = s * inv_scale * inv_scale + extra_sumsq;
-        bool carried_flag = false;
-        if (accumulate) {
-            total += res->sumsq;
-            carried_flag = res->found_inf != 0;
-        }
-        const bool bad = carried_flag || !__builtin_isfinite(total);
-        const double nd = bad ? __builtin_nan("") : sqrt(total);
-        res->sumsq = total;
-        res->norm_d = nd;
-        res->norm = (float)nd;
-        res->found_inf = bad ? 1u : 0u;
+        publish_total(res, s, inv_scale, extra_sumsq, accumulate);
         __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); /* re-arm */
     }
     (void)n_chunks;
+}
+
+/*
+ * Second half of the norm carried by adamw_step_carry_kernel: sums the n wave partials in a
+ * fixed order (each block a strided share, then the blocks in index order by the same ticket
+ * scheme as above) and folds the total into `res`.  8 bytes per 64*VEC elements.
+ */
+__global__ void __launch_bounds__(kThreads)
+fold_partials_kernel(const double *__restrict__ wave_partials, uint64_t n, double inv_scale, double *partials,
+                     uint32_t *ticket, GradResult *res)
+{
+    __shared__ double lds4[4];
+    __shared__ uint32_t is_last;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const double x0 = wave_partials[i], x1 = wave_partials[i + stride];
+        const double x2 = wave_partials[i + 2 * stride], x3 = wave_partials[i + 3 * stride];
+        a0 += x0;
+        a1 += x1;
+        a2 += x2;
+        a3 += x3;
+    }
+    for (; i < n; i += stride) a0 += wave_partials[i];
+    const double bsum = block_sum((a0 + a1) + (a2 + a3), lds4);
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&partials[blockIdx.x], bsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (t == gridDim.x - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    double s = 0.0;
+    for (uint32_t j = threadIdx.x; j < gridDim.x; j += kThreads)
+        s += __hip_atomic_load(&partials[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s = block_sum(s, lds4);
+    if (threadIdx.x == 0) {
+        publish_total(res, s, inv_scale, 0.0, 1u);
+        __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 __global__ void set_result_kernel(GradResult *res, double sumsq, uint32_t found_inf)
@@ -431,6 +580,43 @@ static step_fn pick_step(int dtype, StepVariant s)
 }
 
 bool step_variant_valid(StepVariant s) { return pick_step(kBF16, s) != nullptr; }
+
+typedef void (*carry_fn)(const DevChunk *, const GradResult *, StepConsts, double *, uint64_t);
+
+template <int DT>
+static carry_fn pick_carry(StepVariant s)
+{
+#define AH_CASE(V, B, M) \
+    if (s.vec == V && s.block == B && s.mode == M) return adamw_step_carry_kernel<DT, V, B, M>;
+#define AH_CASES(V, B) AH_CASE(V, B, 0) AH_CASE(V, B, 1)
+    AH_CASES(4, 64) AH_CASES(4, 128) AH_CASES(4, 256)
+    AH_CASES(2, 64) AH_CASES(2, 128) AH_CASES(2, 256)
+    AH_CASES(1, 128) AH_CASES(1, 256) AH_CASES(1, 512)
+#undef AH_CASES
+#undef AH_CASE
+    return nullptr;
+}
+
+hipError_t launch_step_carry(int dtype, StepVariant var, unsigned grid_x, unsigned grid_y, unsigned lds_bytes,
+                             hipStream_t stream, const DevChunk *tab, const GradResult *res, const StepConsts &k,
+                             double *wave_partials, uint64_t slot_base)
+{
+    carry_fn fn = dtype == kFP16 ? pick_carry<kFP16>(var) : pick_carry<kBF16>(var);
+    if (!fn) return hipErrorInvalidValue;
+    if (grid_x == 0 || grid_y == 0) return hipSuccess;
+    hipLaunchKernelGGL(fn, dim3(grid_x, grid_y), dim3(var.block), lds_bytes, stream, tab, res, k, wave_partials,
+                       slot_base);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold(unsigned blocks, hipStream_t stream, const double *wave_partials, uint64_t n,
+                       double inv_scale, double *partials, uint32_t *ticket, GradResult *res)
+{
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(fold_partials_kernel, dim3(blocks), dim3(kThreads), 0, stream, wave_partials, n, inv_scale,
+                       partials, ticket, res);
+    return hipGetLastError();
+}
 
 hipError_t launch_cast(int dtype, unsigned grid_x, unsigned grid_y, unsigned lds_bytes, hipStream_t stream,
                        const DevChunk *tab)

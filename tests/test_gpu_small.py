@@ -636,3 +636,202 @@ def test_two_workspaces_on_two_streams_do_not_interfere():
         for i, st in enumerate(states):
             compare_state(download(md, i), st, "two streams", st["old"], drift_steps=3)
         ws.close()
+
+
+def _two_copies(states, numels):
+    a, b = ModelData(numels), ModelData(numels)
+    for i, st in enumerate(states):
+        upload(a, i, st)
+        upload(b, i, st)
+    return a, b
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+def test_norm_carrying_step_equals_accumulate_then_step(variant, dtype):
+    """autohete_adamw_step_carry must leave the five streams bit-identical to
+    grad_prep_accumulate(next) + adamw_step(current), the next norm equal up to the order of the
+    fp64 additions, and both must match the oracle stepping with the norm held by `current`."""
+    rng = np.random.default_rng(1000 + variant)
+    numels = [int(x) for x in rng.integers(1, 40_000, 19)] + [8192, 256, 1, 8, 65536 + 5, 3 * 16384]
+    scale = 1.0 if dtype == B.AH_BF16 else 64.0
+    states = [random_state(n, dtype, rng, scale=scale) for n in numels]
+    fused, split = _two_copies(states, numels)
+    n = len(numels)
+    cur, nxt, cur2, nxt2 = (B.Workspace(n) for _ in range(4))
+    for w in (cur, cur2):
+        w.tune(B.AH_TUNE_STEP_VARIANT, variant)
+        w.tune(B.AH_TUNE_STEP_BLOCKS_PER_CU, [0, 3, 64][variant % 3])
+    hp = B.hparams(max_grad_norm=0.05, loss_scale=scale)
+    s = stream_handle()
+    carried_in = 0.37                                    # next-norm accumulations start from a non-zero S
+    for w in (cur, cur2):
+        w.autohete_grad_result_set(0.09, 0, s)           # "previous iteration": norm 0.3 -> clipping active
+    for w in (nxt, nxt2):
+        w.autohete_grad_result_set(carried_in, 0, s)
+    cur.autohete_adamw_step_carry(nxt, fused.chunk_array(), n, dtype, 3, hp, s)
+    nxt2.autohete_grad_prep_accumulate(split.chunk_array(), n, dtype, scale, s)
+    cur2.autohete_adamw_step(split.chunk_array(), n, dtype, 3, hp, s)
+    torch.cuda.synchronize()
+    assert cur.autohete_grad_result_get(s) == cur2.autohete_grad_result_get(s)       # untouched by the call
+    sa, na, fa = nxt.autohete_grad_result_get(s)
+    sb, nb, fb = nxt2.autohete_grad_result_get(s)
+    assert fa == fb == 0 and abs(sa - sb) <= 1e-13 * sb
+    ref = carried_in + sum(float(np.sum((oracle.decode(st["grad"], dtype).astype(np.float64) / scale) ** 2))
+                           for st in states)
+    assert abs(sa - ref) <= 1e-12 * ref
+    for i, st in enumerate(states):
+        a, b = download(fused, i), download(split, i)
+        assert all(a[k].tobytes() == b[k].tobytes() for k in STREAMS), (hex(variant), i)
+        old = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(), exp_avg_sq=st["exp_avg_sq"].copy())
+        oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], dtype, 3,
+                           oracle_hp(hp), 0.3, 0)
+        compare_state(a, st, "carry variant=%x chunk=%d" % (variant, i), old)
+    # the same launch again: the carried sum is bit-reproducible
+    nxt.autohete_grad_result_set(carried_in, 0, s)
+    cur.autohete_grad_result_set(0.0, 1, s)              # flagged: no stream may change, squares still gathered
+    before = [download(fused, i) for i in range(n)]
+    cur.autohete_adamw_step_carry(nxt, fused.chunk_array(), n, dtype, 4, hp, s)
+    torch.cuda.synchronize()
+    assert nxt.autohete_grad_result_get(s)[0] == sa
+    for i in range(n):
+        after = download(fused, i)
+        assert all(after[k].tobytes() == before[i][k].tobytes() for k in STREAMS), i
+    for w in (cur, nxt, cur2, nxt2):
+        w.close()
+
+
+def test_norm_carrying_step_lagged_pipeline_against_oracle():
+    """Three iterations of block-by-block stepping, last block first, each block's update clipped
+    with the PREVIOUS iteration's norm while this iteration's is gathered by the same kernels;
+    two workspaces alternate.  Oracle: the same schedule written out (norm of iteration t-1 into
+    the update of iteration t).  A non-finite gradient in iteration 3 must surface in the carried
+    result, and a buffer that has to grow between calls must not disturb anything."""
+    import synthdata
+    d, L, C = 128, 4, 1 << 15
+    sizes = [int(x) for x in synthdata.gpt_tensor_numel(d, L, 500, 32)]
+    off, n_chunks, total, pad = B.autohete_chunk_layout(sizes, C)
+    bounds = [0, off[2]] + [off[2 + 12 * (i + 1)] if 2 + 12 * (i + 1) < len(off) else total for i in range(L)]
+    bounds[-1] = n_chunks * C
+    blocks = list(zip(bounds[:-1], bounds[1:]))
+    rng = np.random.default_rng(77)
+    states = [random_state(C, B.AH_BF16, rng) for _ in range(n_chunks)]
+    for k in states[-1]:
+        states[-1][k][C - pad:] = 0
+    md = ModelData([C] * n_chunks)
+    for i, st in enumerate(states):
+        upload(md, i, st)
+    hp = B.hparams(max_grad_norm=0.02)
+    ws = [B.Workspace(n_chunks + 2), B.Workspace(n_chunks + 2)]
+    s = stream_handle()
+    ws[1].autohete_grad_result_set(0.0, 0, s)            # iteration 1 has no earlier norm: no clipping
+    prev_sumsq = 0.0
+    for it in (1, 2, 3):
+        cur, nxt = ws[it % 2], ws[(it + 1) % 2]
+        if it > 1:
+            for i, st in enumerate(states):              # fresh gradients
+                st["grad"] = random_state(C, B.AH_BF16, rng)["grad"]
+                if i == n_chunks - 1:
+                    st["grad"][C - pad:] = 0
+                if it == 3 and i == 0:
+                    st["grad"][4321] = 0x7FC0            # NaN: seen only in the carried result
+                upload(md, i, dict(grad=st["grad"]))
+        nxt.autohete_grad_result_set(0.0, 0, s)
+        for a, b in reversed(blocks):                    # smallest-to-largest calls also exercise buffer growth
+            tup = md.range_tuples(a, b)
+            cur.autohete_adamw_step_carry(nxt, B.chunk_array(tup), len(tup), B.AH_BF16, it, hp, s)
+        sumsq, norm, flag = nxt.autohete_grad_result_get(s)
+        o_sumsq, o_flag = 0.0, 0
+        for st in states:
+            o_sumsq, o_flag = oracle.grad_accumulate(st["grad"], oracle.BF16, 1.0, o_sumsq, o_flag)
+        assert flag == o_flag == (1 if it == 3 else 0)
+        if not flag:
+            assert abs(sumsq - o_sumsq) <= 1e-12 * o_sumsq
+        if it < 3:                                       # iteration 3 writes NaN into chunk 0 on both sides
+            for i, st in enumerate(states):
+                old = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(),
+                           exp_avg_sq=st["exp_avg_sq"].copy())
+                oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"],
+                                   oracle.BF16, it, oracle_hp(hp), float(np.sqrt(prev_sumsq)), 0)
+                compare_state(download(md, i), st, "lagged it=%d chunk=%d" % (it, i), old)
+                upload(md, i, st)                        # oracle -> device, so each step starts from equal inputs
+        prev_sumsq = o_sumsq
+    for w in ws:
+        w.close()
+
+
+def test_norm_carrying_step_rejects_bad_workspaces():
+    md = ModelData([1024])
+    ws, other = B.Workspace(1), B.Workspace(1)
+    hp = B.hparams()
+    lib = B.raw()
+    args = (md.chunk_array(), 1, B.AH_BF16, 1, ctypes.byref(hp), ctypes.c_void_p(stream_handle()))
+    assert lib.autohete_adamw_step_carry(ws._h, None, *args) == B.AH_EINVAL
+    assert lib.autohete_adamw_step_carry(ws._h, ws._h, *args) == B.AH_EINVAL
+    assert lib.autohete_adamw_step_carry(None, other._h, *args) == B.AH_EINVAL
+    assert lib.autohete_adamw_step_carry(ws._h, other._h, md.chunk_array(), 0, B.AH_BF16, 1, ctypes.byref(hp),
+                                         ctypes.c_void_p(stream_handle())) == B.AH_OK
+    torch.cuda.synchronize()
+    ws.close()
+    other.close()
+
+
+def test_carried_norm_joins_the_result_exactly_once():
+    """The carried squares are folded lazily; whatever call touches ws_next's result next must see
+    them exactly once (reads, accumulations, updates) or drop them (calls that replace the result)."""
+    rng = np.random.default_rng(31)
+    numels = [50_000, 777, 1 << 16]
+    states = [random_state(n, B.AH_BF16, rng) for n in numels]
+    md = ModelData(numels)
+    for i, st in enumerate(states):
+        upload(md, i, st)
+    arr, n, s = md.chunk_array(), len(numels), stream_handle()
+    cur, nxt = B.Workspace(n), B.Workspace(n)
+    hp = B.hparams(lr=0.0, weight_decay=0.0)             # updates leave the master copy alone; gradients are read only
+    S = sum(float(np.sum(oracle.decode(st["grad"], oracle.BF16).astype(np.float64) ** 2)) for st in states)
+
+    def carry(times=1):
+        for _ in range(times):
+            cur.autohete_adamw_step_carry(nxt, arr, n, B.AH_BF16, 1, hp, s)
+
+    cur.autohete_grad_result_set(0.0, 0, s)
+    nxt.autohete_grad_result_set(0.0, 0, s)
+    carry(3)                                             # three calls appended, one fold
+    got = nxt.autohete_grad_result_get(s)[0]
+    assert abs(got - 3 * S) <= 1e-12 * S
+    assert nxt.autohete_grad_result_get(s)[0] == got     # a second read folds nothing more
+    carry()
+    nxt.autohete_grad_prep_accumulate(arr, n, B.AH_BF16, 1.0, s)
+    assert abs(nxt.autohete_grad_result_get(s)[0] - (got + 2 * S)) <= 1e-12 * S
+    carry()
+    nxt.autohete_grad_result_set(5.0, 0, s)              # replaced: the carried sum goes with the old result
+    assert nxt.autohete_grad_result_get(s) == (5.0, float(np.float32(np.sqrt(5.0))), 0)
+    carry()
+    nxt.autohete_grad_prep(arr, n, B.AH_BF16, 1.0, 0.0, s)
+    assert abs(nxt.autohete_grad_result_get(s)[0] - S) <= 1e-12 * S
+    # a different loss scale for later calls: earlier slots keep theirs
+    nxt.autohete_grad_result_set(0.0, 0, s)
+    carry()
+    hp4 = B.hparams(lr=0.0, weight_decay=0.0, loss_scale=4.0)
+    cur.autohete_adamw_step_carry(nxt, arr, n, B.AH_BF16, 1, hp4, s)
+    assert abs(nxt.autohete_grad_result_get(s)[0] - (S + S / 16.0)) <= 1e-12 * S
+    # the workspace that received the sum can clip with it straight away (folded by the update call itself)
+    nxt.autohete_grad_result_set(0.0, 0, s)
+    carry()
+    torch.cuda.synchronize()
+    twin = ModelData(numels)
+    for i in range(n):
+        upload(twin, i, download(md, i))
+    clip = B.hparams(max_grad_norm=1e-3)
+    nxt.autohete_adamw_step(arr, n, B.AH_BF16, 2, clip, s)
+    folded = nxt.autohete_grad_result_get(s)
+    assert abs(folded[0] - S) <= 1e-12 * S and folded[2] == 0
+    cur.autohete_grad_result_set(folded[0], 0, s)
+    cur.autohete_adamw_step(twin.chunk_array(), n, B.AH_BF16, 2, clip, s)
+    torch.cuda.synchronize()
+    for i in range(n):
+        a, b = download(md, i), download(twin, i)
+        assert all(a[k].tobytes() == b[k].tobytes() for k in STREAMS), i
+    assert any(download(md, i)["master"].tobytes() != states[i]["master"].tobytes() for i in range(n))
+    cur.close()
+    nxt.close()

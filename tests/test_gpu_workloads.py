@@ -37,17 +37,37 @@ class Run:
     def __init__(self, name):
         # "<workload>+split": the same workload stepped through autohete_adamw_step_master followed by
         # autohete_cast_params (16-bit parameters materialised on demand), fewer iterations
+        # "<workload>+carry": stepped block by block, last block first, through
+        # autohete_adamw_step_carry: each update clips with the previous iteration's norm while
+        # this iteration's is gathered by the same kernels; two workspaces alternate
         self.split = name.endswith("+split")
+        self.carry = name.endswith("+carry")
+        self.variant = name.split("+")[1] if "+" in name else ""
         name = name.split("+")[0]
         self.w = w = synthdata.workload(name)
-        if self.split:
+        if self.variant:
             w.steps = 3
         self.C = w.chunk_elems
         self.md = ModelData([self.C] * w.n_resident)
         for c in range(w.n_resident):
             fill_device_chunk(self.md, w, c)
-        self.ws = B.Workspace(w.n_resident)
+        self.ws = B.Workspace(w.n_resident + 2)
         self.arr = self.md.chunk_array()
+        if self.carry:
+            assert w.n_resident == w.n_chunks and not w.inject
+            self.ws_other = B.Workspace(w.n_resident + 2)
+            self.ws_other.autohete_grad_result_set(0.0, 0, stream_handle())   # no norm before iteration 1
+            self.prev_norm = 0.0
+            off, _, total, _ = B.autohete_chunk_layout([int(x) for x in w.tensor_numel], self.C)
+            n_layers = (len(off) - 2) // 12
+            bounds = [0, off[2]] + [off[2 + 12 * (i + 1)] if 2 + 12 * (i + 1) < len(off) else total
+                                    for i in range(n_layers)]
+            bounds[-1] = w.n_chunks * self.C             # the last block also carries the padding
+            self.parts = []
+            for a, b in zip(bounds[:-1], bounds[1:]):
+                tup = self.md.range_tuples(a, b)
+                self.parts.append((B.chunk_array(tup), len(tup)))
+            self.parts.reverse()
         k = SAMPLES[name]
         if k is None:
             self.sample = list(range(w.n_resident))
@@ -97,12 +117,19 @@ class Run:
             extra = float(np.float32(s))
         hp = B.hparams(**w.hparams, loss_scale=scale)
         before = self.checksums() if it in w.inject else None
-        gn, gf = self.ws.autohete_grad_prep(self.arr, w.n_resident, w.dtype, scale, extra, stream_handle(),
-                                            want_result=True)
+        if self.carry:
+            cur, nxt = (self.ws_other, self.ws) if it % 2 else (self.ws, self.ws_other)
+            nxt.autohete_grad_result_set(0.0, 0, stream_handle())
+            for arr, k in self.parts:
+                cur.autohete_adamw_step_carry(nxt, arr, k, w.dtype, self.t, hp, stream_handle())
+            _, gn, gf = nxt.autohete_grad_result_get(stream_handle())
+        else:
+            gn, gf = self.ws.autohete_grad_prep(self.arr, w.n_resident, w.dtype, scale, extra, stream_handle(),
+                                                want_result=True)
         if self.split:
             self.ws.autohete_adamw_step_master(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
             self.ws.autohete_cast_params(self.arr, w.n_resident, w.dtype, stream_handle())
-        else:
+        elif not self.carry:
             self.ws.autohete_adamw_step(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
         torch.cuda.synchronize()
         # oracle: norm over every resident chunk, then the sampled chunks element by element
@@ -126,6 +153,9 @@ class Run:
                                    oracle_hp(hp), on, of)
                 if not of:
                     oracle.cast_chunk(h["master"], h["param_lp"], w.dtype)
+            elif self.carry:     # the norm of the previous iteration (none before the first)
+                oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
+                                   oracle_hp(hp), self.prev_norm, 0)
             else:
                 oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
                                    oracle_hp(hp), on, of)
@@ -147,6 +177,8 @@ class Run:
             self.scale = scale / 2.0
         else:
             self.t += 1
+        if self.carry:
+            self.prev_norm = on
         self.done = it
 
     def finish(self):
@@ -164,13 +196,15 @@ class Run:
                                                             "master_relaxed", "exp_avg_relaxed", "exp_avg_sq_relaxed")}
         out_dir = os.environ.get("AUTOHETE_PARITY_REPORT_DIR", "parity_reports")
         os.makedirs(out_dir, exist_ok=True)
-        with open(os.path.join(out_dir, "parity_%s%s.txt" % (w.name, "_split" if self.split else "")), "w") as fh:
+        with open(os.path.join(out_dir, "parity_%s%s.txt" % (w.name, "_" + self.variant if self.variant else "")), "w") as fh:
             fh.write("workload %s: %d iterations, %d updates, sampled chunks %s (free-running: %s)\n" %
                      (w.name, self.done, self.t - 1, self.sample, self.free))
             fh.write("element-steps compared: %d\nworst error vs oracle (ulp, cancelled elements aside): %s\n"
                      "bitwise mismatches / elements judged with the cancellation or drift allowance: %s\n" %
                      (n, worst, mism))
         self.ws.close()
+        if self.carry:
+            self.ws_other.close()
 
 
 _runs = {}
@@ -187,7 +221,7 @@ def get_run(name):
 
 
 def cases():
-    for name in synthdata.WORKLOADS + ("gpt-1.3b+split",):
+    for name in synthdata.WORKLOADS + ("gpt-1.3b+split", "gpt-6.7b+carry"):
         w = synthdata.workload(name.split("+")[0])
         if "+" in name:
             w.steps = 3
