@@ -835,3 +835,42 @@ def test_carried_norm_joins_the_result_exactly_once():
     assert any(download(md, i)["master"].tobytes() != states[i]["master"].tobytes() for i in range(n))
     cur.close()
     nxt.close()
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_nothing_is_written_outside_the_chunks(variant):
+    """Every slab is filled with a byte pattern, ragged chunks are placed into it with gaps between
+    them (and a guard region after the last), and every entry point runs over them: all bytes that
+    belong to no chunk must keep the pattern, for every kernel variant and both 16-bit formats."""
+    rng = np.random.default_rng(4242 + variant)
+    sizes = [1, 3, 7, 8, 9, 63, 65, 127, 255, 257, 511, 1023, 1025, 2047, 4097, 8191, 65536 + 5, 1000, 128]
+    numels = sizes + [256]                                   # the last one is never given to the library
+    real = list(range(len(sizes)))
+    for dtype in (B.AH_BF16, B.AH_FP16):
+        md = ModelData(numels)
+        for t in md.slab.values():
+            t.view(torch.uint8).fill_(0xA5)
+        for i in real:
+            upload(md, i, random_state(numels[i], dtype, rng))
+        inside = torch.zeros(md.slab_elems, dtype=torch.bool, device=md.device)
+        for i in real:
+            inside[md.offset[i]:md.offset[i] + numels[i]] = True
+        ws, other = B.Workspace(len(numels)), B.Workspace(len(numels))
+        ws.tune(B.AH_TUNE_STEP_VARIANT, variant)
+        arr, n, s = md.chunk_array(real), len(real), stream_handle()
+        hp = B.hparams()
+        ws.autohete_grad_prep(arr, n, dtype, 1.0, 0.0, s)
+        ws.autohete_adamw_step(arr, n, dtype, 1, hp, s)
+        ws.autohete_adamw_step_master(arr, n, dtype, 2, hp, s)
+        ws.autohete_cast_params(arr, n, dtype, s)
+        other.autohete_grad_result_set(0.0, 0, s)
+        ws.autohete_adamw_step_carry(other, arr, n, dtype, 3, hp, s)
+        other.autohete_grad_prep_accumulate(arr, n, dtype, 1.0, s)
+        torch.cuda.synchronize()
+        assert other.autohete_grad_result_get(s)[2] == 0
+        for name, t in md.slab.items():
+            width = t.element_size()
+            outside = t.view(torch.uint8).view(-1, width)[~inside]
+            assert bool((outside == 0xA5).all()), (hex(variant), dtype, name)
+        ws.close()
+        other.close()
