@@ -1,7 +1,7 @@
 /*
  * autohete_api.hip -- host side of libautohete.so: the C ABI declared in include/autohete.h.
  * Argument validation, the chunk layout, the workspace (device scratch + device copies of the
- * chunk tables, re-uploaded only when a call's chunk list differs from the previous one), and
+ * chunk tables, kept by content so that a list seen before is not uploaded again), and
  * the fp64 preparation of the per-launch constants.  All per-element work is in the kernels.
  */
 #include <math.h>
@@ -21,28 +21,39 @@ struct autohete_ws {
     int device = 0;
     int n_cu = 0;
     uint64_t max_chunks = 0;
-    /* slot 0: table of the last grad_prep call, slot 1: of the last adamw_step call */
-    DevChunk *d_tab[2] = {nullptr, nullptr};
-    /* Pinned staging for the asynchronous table uploads: a small ring per slot, so that a caller
-     * that changes its chunk list on every call (per-block stepping) does not have to wait for
-     * the previous upload -- queued behind earlier kernels -- before it can stage the next one. */
+    /* Device copies of chunk tables, kept by content: a caller that cycles through a few chunk
+     * lists (one per transformer block, or one per resident gradient buffer) uploads each list
+     * once.  Least recently used entry is replaced. */
+    struct Group { uint32_t first, rows; uint64_t max_tiles; }; /* rows [first, first+rows) share grid_x */
+    struct Table {
+        DevChunk *d = nullptr;
+        std::vector<DevChunk> h;                /* what d holds */
+        int kind = -1;                          /* which builder made it (layouts differ) */
+        uint32_t tile_elems = 0;                /* ... and for which tile size */
+        uint64_t hash = 0, last_use = 0;
+        std::vector<Group> groups;              /* launch groups (step / cast tables) */
+        uint64_t tiles = 0;                     /* all tiles of the table */
+        hipEvent_t uploaded = nullptr;          /* the upload into d has completed */
+        hipStream_t upload_stream = nullptr;
+        bool upload_pending = false;
+    };
+    std::vector<Table> tables;
+    uint64_t use_clock = 0;
+    /* Pinned staging for the asynchronous uploads: a small ring, so that a caller that brings a
+     * new chunk list with every call does not have to wait for the previous upload -- queued
+     * behind earlier kernels -- before it can stage the next one. */
     static constexpr int kRing = 8;
     int ring_depth = 1;
-    int ring_next[2] = {0, 0};
-    DevChunk *h_stage[2][kRing] = {};
-    hipEvent_t staged[2][kRing] = {};           /* upload from h_stage[slot][i] has completed */
-    bool staged_pending[2][kRing] = {};
-    std::vector<DevChunk> h_last[2];            /* what d_tab holds */
+    int ring_next = 0;
+    DevChunk *h_stage[kRing] = {};
+    hipEvent_t staged[kRing] = {};              /* upload from h_stage[i] has completed */
+    bool staged_pending[kRing] = {};
     double *d_partials = nullptr;
     uint32_t *d_ticket = nullptr;
     GradResult *d_res = nullptr;
     GradResult *h_res = nullptr;                /* pinned read-back */
     int64_t tune_step_blocks_per_cu = 0, tune_prep_blocks = 0, tune_step_variant = 0, tune_cast_blocks_per_cu = 0;
     size_t lds_per_cu = 0;
-    /* launch groups of the current step table: rows [first, first+rows) share grid_x */
-    struct Group { uint32_t first, rows; uint64_t max_tiles; };
-    std::vector<Group> step_groups;
-    uint64_t step_tiles = 0;                    /* tiles of the current step table, all groups */
     /* Norm carried INTO this workspace by autohete_adamw_step_carry calls: one fp64 slot per
      * wavefront of those calls, appended call after call and summed into d_res by one fold kernel
      * when the result is next needed.  Grown on demand, never shrunk. */
@@ -98,33 +109,75 @@ void fill_row(DevChunk &d, const autohete_chunk &c, uint64_t tile_begin)
     d.reserved = 0;
 }
 
-/* Upload `tab` into table slot `slot` unless the device copy already holds exactly that. */
-int upload_table(autohete_ws *ws, int slot, std::vector<DevChunk> &tab, hipStream_t stream, bool *changed)
+enum : int { kPrepTable = 0, kStepTable = 1 };
+
+uint64_t table_hash(const std::vector<DevChunk> &tab, int kind, uint32_t tile_elems)
 {
-    std::vector<DevChunk> &last = ws->h_last[slot];
-    *changed = !(last.size() == tab.size() &&
-                 memcmp(last.data(), tab.data(), tab.size() * sizeof(DevChunk)) == 0);
-    if (!*changed) return AH_OK;
-    const int r = ws->ring_next[slot];
-    ws->ring_next[slot] = (r + 1) % ws->ring_depth;
-    if (ws->staged_pending[slot][r]) { /* an upload issued ring_depth calls ago may still read this buffer */
-        if (hipEventSynchronize(ws->staged[slot][r]) != hipSuccess) return AH_EHIP;
-        ws->staged_pending[slot][r] = false;
+    uint64_t h = 0x9E3779B97F4A7C15ull ^ ((uint64_t)kind << 32 | tile_elems);
+    const uint64_t *w = reinterpret_cast<const uint64_t *>(tab.data());
+    const size_t n = tab.size() * (sizeof(DevChunk) / sizeof(uint64_t));
+    for (size_t i = 0; i < n; ++i) {
+        h = (h ^ w[i]) * 0xFF51AFD7ED558CCDull;
+        h ^= h >> 29;
     }
-    memcpy(ws->h_stage[slot][r], tab.data(), tab.size() * sizeof(DevChunk));
-    if (hipMemcpyAsync(ws->d_tab[slot], ws->h_stage[slot][r], tab.size() * sizeof(DevChunk),
-                       hipMemcpyHostToDevice, stream) != hipSuccess)
+    return h;
+}
+
+/* The device copy of `tab`: an entry that already holds exactly this content, else the least
+ * recently used entry, overwritten by an upload enqueued on `stream`.  *fresh tells the caller
+ * that it still has to fill in the entry's launch groups. */
+int find_or_upload(autohete_ws *ws, int kind, uint32_t tile_elems, std::vector<DevChunk> &tab, hipStream_t stream,
+                   autohete_ws::Table **out, bool *fresh)
+{
+    const uint64_t h = table_hash(tab, kind, tile_elems);
+    autohete_ws::Table *lru = &ws->tables[0];
+    for (autohete_ws::Table &t : ws->tables) {
+        if (t.kind == kind && t.tile_elems == tile_elems && t.hash == h && t.h.size() == tab.size() &&
+            memcmp(t.h.data(), tab.data(), tab.size() * sizeof(DevChunk)) == 0) {
+            /* uploaded on another stream and perhaps still on its way: order this stream after it */
+            if (t.upload_pending && t.upload_stream != stream) {
+                if (hipEventQuery(t.uploaded) == hipSuccess) t.upload_pending = false;
+                else if (hipStreamWaitEvent(stream, t.uploaded, 0) != hipSuccess) return AH_EHIP;
+                (void)hipGetLastError(); /* hipErrorNotReady from the query is not an error */
+            }
+            t.last_use = ++ws->use_clock;
+            *out = &t;
+            *fresh = false;
+            return AH_OK;
+        }
+        if (t.last_use < lru->last_use) lru = &t;
+    }
+    const int r = ws->ring_next;
+    ws->ring_next = (r + 1) % ws->ring_depth;
+    if (ws->staged_pending[r]) { /* an upload issued ring_depth misses ago may still read this buffer */
+        if (hipEventSynchronize(ws->staged[r]) != hipSuccess) return AH_EHIP;
+        ws->staged_pending[r] = false;
+    }
+    memcpy(ws->h_stage[r], tab.data(), tab.size() * sizeof(DevChunk));
+    lru->kind = -1; /* not a valid entry until everything below has succeeded */
+    if (hipMemcpyAsync(lru->d, ws->h_stage[r], tab.size() * sizeof(DevChunk), hipMemcpyHostToDevice, stream) !=
+            hipSuccess ||
+        hipEventRecord(ws->staged[r], stream) != hipSuccess || hipEventRecord(lru->uploaded, stream) != hipSuccess)
         return AH_EHIP;
-    if (hipEventRecord(ws->staged[slot][r], stream) != hipSuccess) return AH_EHIP;
-    ws->staged_pending[slot][r] = true;
-    last.swap(tab);
+    ws->staged_pending[r] = true;
+    lru->h.swap(tab);
+    lru->hash = h;
+    lru->kind = kind;
+    lru->tile_elems = tile_elems;
+    lru->upload_stream = stream;
+    lru->upload_pending = true;
+    lru->groups.clear();
+    lru->tiles = 0;
+    lru->last_use = ++ws->use_clock;
+    *out = lru;
+    *fresh = true;
     return AH_OK;
 }
 
 /* Table of the prep kernel: rows in the caller's order, each with the index of its first tile;
  * row n is a sentinel holding the total tile count. */
 int build_prep_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
-                     hipStream_t stream, uint64_t *total_tiles)
+                     hipStream_t stream, autohete_ws::Table **out)
 {
     if (n > ws->max_chunks) return AH_ENOMEM;
     if (n && !chunks) return AH_EINVAL;
@@ -138,16 +191,17 @@ int build_prep_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
     }
     memset(&tab[n], 0, sizeof(DevChunk));
     tab[n].tile_begin = tiles;
-    *total_tiles = tiles;
-    bool changed;
-    return upload_table(ws, 0, tab, stream, &changed);
+    bool fresh;
+    int rc = find_or_upload(ws, kPrepTable, tile_elems, tab, stream, out, &fresh);
+    if (rc == AH_OK && fresh) (*out)->tiles = tiles;
+    return rc;
 }
 
 /* Table of the step kernel: one row per chunk, rows grouped by ceil(log2(tile count)) so that
  * each group can be launched as a 2-D grid (x = tile, y = row) in which at most half of the
  * blocks fall beyond the end of their chunk.  Equal-sized chunks form a single group. */
 int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
-                     unsigned need, hipStream_t stream)
+                     unsigned need, hipStream_t stream, autohete_ws::Table **out)
 {
     if (n > ws->max_chunks) return AH_ENOMEM;
     if (n && !chunks) return AH_EINVAL;
@@ -184,7 +238,7 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
     }
     memset(&tab[n], 0, sizeof(DevChunk));
     tab[n].tile_begin = tile_run;
-    std::vector<autohete_ws::Group> groups;
+    std::vector<autohete_ws::Group> groups; /* built before the entry is touched: this may throw */
     for (int b = 0; b < 65; ++b) {
         for (uint32_t first = start[b]; first < start[b] + count[b]; first += 65535u) {
             const uint32_t rows = std::min<uint32_t>(65535u, start[b] + count[b] - first);
@@ -193,11 +247,11 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
             groups.push_back({first, rows, mx});
         }
     }
-    bool changed;
-    int rc = upload_table(ws, 1, tab, stream, &changed);
-    if (rc != AH_OK) return rc;
-    ws->step_groups.swap(groups);
-    ws->step_tiles = tile_run;
+    bool fresh;
+    int rc = find_or_upload(ws, kStepTable, tile_elems, tab, stream, out, &fresh);
+    if (rc != AH_OK || !fresh) return rc;
+    (*out)->groups.swap(groups);
+    (*out)->tiles = tile_run;
     return AH_OK;
 }
 
@@ -321,13 +375,21 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
     ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
     bool ok = true;
     const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
+    /* as many cached tables and staging buffers as fit a few MB, at least the two a prep + step pair needs */
+    const size_t n_tables = std::min<size_t>(32, std::max<size_t>(2, (8u << 20) / tab_bytes));
     ws->ring_depth = (int)std::min<size_t>(autohete_ws::kRing, std::max<size_t>(1, (4u << 20) / tab_bytes));
-    for (int s = 0; ok && s < 2; ++s) {
-        ok = hipMalloc(&ws->d_tab[s], tab_bytes) == hipSuccess;
-        for (int r = 0; ok && r < ws->ring_depth; ++r)
-            ok = hipHostMalloc(&ws->h_stage[s][r], tab_bytes, hipHostMallocDefault) == hipSuccess &&
-                 hipEventCreateWithFlags(&ws->staged[s][r], hipEventDisableTiming) == hipSuccess;
+    try {
+        ws->tables.resize(n_tables);
+    } catch (...) {
+        delete ws;
+        return AH_ENOMEM;
     }
+    for (autohete_ws::Table &t : ws->tables)
+        ok = ok && hipMalloc(&t.d, tab_bytes) == hipSuccess &&
+             hipEventCreateWithFlags(&t.uploaded, hipEventDisableTiming) == hipSuccess;
+    for (int r = 0; ok && r < ws->ring_depth; ++r)
+        ok = hipHostMalloc(&ws->h_stage[r], tab_bytes, hipHostMallocDefault) == hipSuccess &&
+             hipEventCreateWithFlags(&ws->staged[r], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipMalloc(&ws->d_partials, ah::kMaxPartials * sizeof(double)) == hipSuccess &&
          hipMalloc(&ws->d_ticket, 256) == hipSuccess && hipMalloc(&ws->d_res, 256) == hipSuccess &&
          hipHostMalloc(&ws->h_res, sizeof(GradResult), hipHostMallocDefault) == hipSuccess;
@@ -353,12 +415,13 @@ int autohete_ws_destroy(autohete_ws *ws)
     if (!ws) return AH_EINVAL;
     DeviceGuard g(ws->device);
     (void)hipDeviceSynchronize();
-    for (int s = 0; s < 2; ++s) {
-        if (ws->d_tab[s]) (void)hipFree(ws->d_tab[s]);
-        for (int r = 0; r < autohete_ws::kRing; ++r) {
-            if (ws->h_stage[s][r]) (void)hipHostFree(ws->h_stage[s][r]);
-            if (ws->staged[s][r]) (void)hipEventDestroy(ws->staged[s][r]);
-        }
+    for (autohete_ws::Table &t : ws->tables) {
+        if (t.d) (void)hipFree(t.d);
+        if (t.uploaded) (void)hipEventDestroy(t.uploaded);
+    }
+    for (int r = 0; r < autohete_ws::kRing; ++r) {
+        if (ws->h_stage[r]) (void)hipHostFree(ws->h_stage[r]);
+        if (ws->staged[r]) (void)hipEventDestroy(ws->staged[r]);
     }
     if (ws->d_partials) (void)hipFree(ws->d_partials);
     if (ws->d_wave_partials) (void)hipFree(ws->d_wave_partials);
@@ -415,7 +478,7 @@ static int prep_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     DeviceGuard g(ws->device);
     if (!g.ok) return AH_EHIP;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    uint64_t tiles = 0;
+    autohete_ws::Table *tab = nullptr;
     int rc;
     if (accumulate) {
         if ((rc = flush_carried(ws, stream)) != AH_OK) return rc;
@@ -423,7 +486,7 @@ static int prep_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
         ws->carried_slots = 0; /* the result is replaced: a carried sum not folded yet goes with it */
     }
     try {
-        rc = build_prep_table(ws, chunks, n_chunks, ah::prep_tile_elems(), stream, &tiles);
+        rc = build_prep_table(ws, chunks, n_chunks, ah::prep_tile_elems(), stream, &tab);
     } catch (...) { /* std::bad_alloc from the host-side table: nothing may be thrown across the C ABI */
         return AH_ENOMEM;
     }
@@ -431,10 +494,11 @@ static int prep_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
 
     /* One 256-thread block per CU, each with 32 KB of loads in flight: the measured optimum for
      * a read-only stream on this chip (more resident blocks widen the window and lose bandwidth). */
+    const uint64_t tiles = tab->tiles;
     uint64_t blocks = ws->tune_prep_blocks ? (uint64_t)ws->tune_prep_blocks : (uint64_t)ws->n_cu;
     if (blocks > (uint64_t)ah::kMaxPartials) blocks = ah::kMaxPartials;
     if (blocks > tiles) blocks = tiles;
-    if (ah::launch_prep(lowp_dtype, (unsigned)blocks, stream, ws->d_tab[0], (uint32_t)n_chunks, tiles,
+    if (ah::launch_prep(lowp_dtype, (unsigned)blocks, stream, tab->d, (uint32_t)n_chunks, tiles,
                         1.0 / (double)loss_scale, extra_sumsq, accumulate, ws->d_partials, ws->d_ticket,
                         ws->d_res) != hipSuccess)
         return AH_EHIP;
@@ -475,10 +539,11 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     ah::StepVariant var;
     if (!decode_variant(ws->tune_step_variant, &var)) return AH_EINVAL;
     var.write_back = write_back;
+    autohete_ws::Table *tab = nullptr;
     int rc;
     try {
         rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block),
-                              kGrad | kMaster | kMom1 | kMom2 | (write_back ? kLowp : 0u), stream);
+                              kGrad | kMaster | kMom1 | kMom2 | (write_back ? kLowp : 0u), stream, &tab);
     } catch (...) {
         return AH_ENOMEM;
     }
@@ -505,20 +570,20 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     const unsigned lds = lds_for_cap(ws, ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu
                                          : carry_to ? kDefaultCarryBlocksPerCu : kDefaultBlocksPerCu);
     if (!carry_to) {
-        for (const autohete_ws::Group &grp : ws->step_groups) {
+        for (const autohete_ws::Group &grp : tab->groups) {
             if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
-                                ws->d_tab[1] + grp.first, ws->d_res, k) != hipSuccess)
+                                tab->d + grp.first, ws->d_res, k) != hipSuccess)
                 return AH_EHIP;
         }
         return AH_OK;
     }
     /* One slot per wavefront, appended to what earlier calls carried into the same workspace. */
     uint64_t base = 0;
-    rc = reserve_carried(carry_to, ws->step_tiles * (uint64_t)(var.block / 64), k.inv_scale, stream, &base);
+    rc = reserve_carried(carry_to, tab->tiles * (uint64_t)(var.block / 64), k.inv_scale, stream, &base);
     if (rc != AH_OK) return rc;
-    for (const autohete_ws::Group &grp : ws->step_groups) {
+    for (const autohete_ws::Group &grp : tab->groups) {
         if (ah::launch_step_carry(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
-                                  ws->d_tab[1] + grp.first, ws->d_res, k, carry_to->d_wave_partials, base) !=
+                                  tab->d + grp.first, ws->d_res, k, carry_to->d_wave_partials, base) !=
             hipSuccess)
             return AH_EHIP;
     }
@@ -552,17 +617,18 @@ int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t
     DeviceGuard g(ws->device);
     if (!g.ok) return AH_EHIP;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    autohete_ws::Table *tab = nullptr;
     int rc;
     try {
-        rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, kLowp | kMaster, stream);
+        rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, kLowp | kMaster, stream, &tab);
     } catch (...) {
         return AH_ENOMEM;
     }
     if (rc != AH_OK) return rc;
     const unsigned lds = lds_for_cap(ws, ws->tune_cast_blocks_per_cu ? ws->tune_cast_blocks_per_cu
                                                                       : kDefaultCastBlocksPerCu);
-    for (const autohete_ws::Group &grp : ws->step_groups) {
-        if (ah::launch_cast(lowp_dtype, (unsigned)grp.max_tiles, grp.rows, lds, stream, ws->d_tab[1] + grp.first) !=
+    for (const autohete_ws::Group &grp : tab->groups) {
+        if (ah::launch_cast(lowp_dtype, (unsigned)grp.max_tiles, grp.rows, lds, stream, tab->d + grp.first) !=
             hipSuccess)
             return AH_EHIP;
     }

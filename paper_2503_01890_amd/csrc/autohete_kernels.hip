@@ -456,11 +456,16 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
         }
         const uint64_t e0 = (w - c_begin) * kTile;
         if (e0 + kTile <= numel) {
+            /* All U loads are issued, in order, before the first square; the squares then follow in
+             * the same order, each group waiting only for its own load (vmcnt U-1, U-2, ...), so the
+             * arithmetic runs under the arrival of the later loads.  The barriers pin that order:
+             * left alone, the scheduler starts with a late load and waits for nearly all of them. */
             u32x4 g[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
                 g[u] = ld<true>((const AH_GLOBAL u32x4 *)(grad + e0 + (uint64_t)u * kSub + threadIdx.x * kPrepVec));
-            __builtin_amdgcn_sched_barrier(0); /* all U loads in flight before the first square */
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -470,6 +475,7 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
                     acc0 += (double)lo * (double)lo;
                     acc1 += (double)hi * (double)hi;
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
             const uint64_t end = e0 + kTile < numel ? e0 + kTile : numel;

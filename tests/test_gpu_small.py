@@ -874,3 +874,38 @@ def test_nothing_is_written_outside_the_chunks(variant):
             assert bool((outside == 0xA5).all()), (hex(variant), dtype, name)
         ws.close()
         other.close()
+
+
+def test_more_chunk_lists_than_cached_tables_and_a_second_stream():
+    """Chunk tables are kept on the device by content and replaced least-recently-used.  Forty
+    single-chunk lists, cycled three times, overflow that cache; every call must still see its own
+    list.  A list first used on one stream and at once on another must be complete there too."""
+    rng = np.random.default_rng(808)
+    numels = [int(x) for x in rng.integers(100, 30_000, 40)]
+    states = [random_state(n, B.AH_BF16, rng) for n in numels]
+    md = ModelData(numels)
+    for i, st in enumerate(states):
+        upload(md, i, st)
+    ws = B.Workspace(4)
+    hp = B.hparams(max_grad_norm=0.01)
+    s = stream_handle()
+    for step in (1, 2, 3):
+        for i in range(40):
+            arr = md.chunk_array([i])
+            ws.autohete_grad_prep(arr, 1, B.AH_BF16, 1.0, 0.0, s)
+            ws.autohete_adamw_step(arr, 1, B.AH_BF16, step, hp, s)
+        torch.cuda.synchronize()
+        for i, st in enumerate(states):
+            run_oracle([st], B.AH_BF16, step, hp)
+            compare_state(download(md, i), st, "cycle %d chunk %d" % (step, i), st["old"], drift_steps=step - 1)
+    side = torch.cuda.Stream()                           # default priority
+    torch.cuda.synchronize()
+    fresh = md.chunk_array([3, 5, 8])                    # a list this workspace has not seen
+    ws.autohete_grad_prep(fresh, 3, B.AH_BF16, 1.0, 0.0, s)            # upload enqueued on the first stream
+    with torch.cuda.stream(side):
+        ws.autohete_grad_prep(fresh, 3, B.AH_BF16, 1.0, 0.0, side.cuda_stream)   # found in the cache
+        got = ws.autohete_grad_result_get(side.cuda_stream)[0]
+    torch.cuda.synchronize()
+    ref = sum(float(np.sum(oracle.decode(states[i]["grad"], oracle.BF16).astype(np.float64) ** 2)) for i in (3, 5, 8))
+    assert abs(got - ref) <= 1e-12 * ref
+    ws.close()
