@@ -37,7 +37,11 @@ def parse():
                     help="fused: prep + adamw_step (headline).  split: prep + adamw_step_master (no 16-bit "
                          "write-back) + cast_params, the on-demand 16-bit materialisation variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--grad-slabs", type=int, default=0, help="gradient slabs kept resident (0 = one per step if they fit)")
+    ap.add_argument("--grad-slabs", type=int, default=0, help="gradient sets kept resident (0 = one per step if they fit)")
+    ap.add_argument("--layout", choices=("group", "slab"), default="group",
+                    help="HBM layout of the model data: groups of chunks, each group holding one run per stream "
+                         "(default), or one slab per stream")
+    ap.add_argument("--group-chunks", type=int, default=0, help="chunks per group of the group layout (0 = by size)")
     ap.add_argument("--step-variant", type=lambda x: int(x, 0), default=0, help="AH_TUNE_STEP_VARIANT value (0 = default)")
     ap.add_argument("--blocks-per-cu", type=int, default=0, help="AH_TUNE_STEP_BLOCKS_PER_CU (0 = default)")
     ap.add_argument("--prep-blocks", type=int, default=0, help="AH_TUNE_PREP_BLOCKS (0 = default)")
@@ -145,7 +149,7 @@ def main():
     grad_bytes = elems * 2
     fit = int((free - state_bytes - (6 << 30)) // grad_bytes)
     n_sets = max(1, min(total_steps, fit, args.grad_slabs or total_steps))
-    md = ModelData([C] * nres, n_grad_sets=n_sets)
+    md = ModelData([C] * nres, n_grad_sets=n_sets, layout=args.layout, group_chunks=args.group_chunks or None)
     for c in range(nres):
         synthdata.fill_gpu(md.ptr("param_lp", c), C, w.spec_param_lp(c), stream)
         synthdata.fill_gpu(md.ptr("master", c), C, w.spec_master(c), stream)
@@ -189,8 +193,13 @@ def main():
 
     for i in range(args.warmup):
         one_step(i, i + 1)
-    torch.cuda.synchronize()
+    # Timing events are created and recorded once here, outside the timed region: the first record of
+    # a timing event in a process can take tens of milliseconds on the host (runtime set-up).
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for ev in events:
+        for e in ev:
+            e.record()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
         one_step(args.warmup + k, args.warmup + k + 1, events[k])
@@ -219,7 +228,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.n_valid, "resident_params": n_valid,
                    "chunks": nres, "chunk_elems": C, "lowp": "bf16" if w.dtype == B.AH_BF16 else "fp16",
-                   "path": args.path, "grad_slabs_resident": n_sets, "grad_norm": norm,
+                   "path": args.path, "layout": args.layout if args.layout == "slab" else "groups of %d chunks" % md.group_chunks, "grad_slabs_resident": n_sets, "grad_norm": norm,
                    "hparams": dict(w.hparams, loss_scale=w.loss_scale)},
         "hbm": {"achieved_GBps": both_gbps, "frac_of_peak": both_gbps / HBM_PEAK_GBPS,
                 "bytes_per_param": total_bytes,

@@ -589,7 +589,7 @@ def test_seventy_thousand_tiny_chunks_cross_the_grid_row_limit():
     numels = [int(x) for x in rng.integers(1, 40, n_chunks)]
     total = sum(numels)
     flat = random_state(total, B.AH_BF16, rng)
-    md = ModelData(numels)
+    md = ModelData(numels, layout="slab")
     # upload through the slabs directly: chunk i sits at md.offset[i]
     idx = np.concatenate([np.arange(o, o + n) for o, n in zip(md.offset, numels)])
     for s in STREAMS:
@@ -847,14 +847,16 @@ def test_nothing_is_written_outside_the_chunks(variant):
     numels = sizes + [256]                                   # the last one is never given to the library
     real = list(range(len(sizes)))
     for dtype in (B.AH_BF16, B.AH_FP16):
-        md = ModelData(numels)
-        for t in md.slab.values():
-            t.view(torch.uint8).fill_(0xA5)
+        md = ModelData(numels, layout=("group", "slab")[variant % 2], group_chunks=1 + variant % 5)
+        for t in md.storages():
+            t.fill_(0xA5)
         for i in real:
             upload(md, i, random_state(numels[i], dtype, rng))
-        inside = torch.zeros(md.slab_elems, dtype=torch.bool, device=md.device)
+        inside = [torch.zeros(t.numel(), dtype=torch.bool, device=md.device) for t in md.storages()]
         for i in real:
-            inside[md.offset[i]:md.offset[i] + numels[i]] = True
+            for name in STREAMS:
+                k, a, b = md.byte_span(name, i)
+                inside[k][a:b] = True
         ws, other = B.Workspace(len(numels)), B.Workspace(len(numels))
         ws.tune(B.AH_TUNE_STEP_VARIANT, variant)
         arr, n, s = md.chunk_array(real), len(real), stream_handle()
@@ -868,10 +870,8 @@ def test_nothing_is_written_outside_the_chunks(variant):
         other.autohete_grad_prep_accumulate(arr, n, dtype, 1.0, s)
         torch.cuda.synchronize()
         assert other.autohete_grad_result_get(s)[2] == 0
-        for name, t in md.slab.items():
-            width = t.element_size()
-            outside = t.view(torch.uint8).view(-1, width)[~inside]
-            assert bool((outside == 0xA5).all()), (hex(variant), dtype, name)
+        for k, t in enumerate(md.storages()):
+            assert bool((t[~inside[k]] == 0xA5).all()), (hex(variant), dtype, k)
         ws.close()
         other.close()
 
