@@ -38,6 +38,7 @@ struct autohete_ws {
         bool upload_pending = false;
     };
     std::vector<Table> tables;
+    DevChunk *d_tables = nullptr;               /* one allocation; tables[i].d points into it */
     uint64_t use_clock = 0;
     /* Pinned staging for the asynchronous uploads: a small ring, so that a caller that brings a
      * new chunk list with every call does not have to wait for the previous upload -- queued
@@ -384,9 +385,11 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
         delete ws;
         return AH_ENOMEM;
     }
-    for (autohete_ws::Table &t : ws->tables)
-        ok = ok && hipMalloc(&t.d, tab_bytes) == hipSuccess &&
-             hipEventCreateWithFlags(&t.uploaded, hipEventDisableTiming) == hipSuccess;
+    ok = hipMalloc(&ws->d_tables, n_tables * tab_bytes) == hipSuccess; /* rows are 64 bytes: every table stays aligned */
+    for (size_t i = 0; ok && i < n_tables; ++i) {
+        ws->tables[i].d = ws->d_tables + i * (max_chunks + 1);
+        ok = hipEventCreateWithFlags(&ws->tables[i].uploaded, hipEventDisableTiming) == hipSuccess;
+    }
     for (int r = 0; ok && r < ws->ring_depth; ++r)
         ok = hipHostMalloc(&ws->h_stage[r], tab_bytes, hipHostMallocDefault) == hipSuccess &&
              hipEventCreateWithFlags(&ws->staged[r], hipEventDisableTiming) == hipSuccess;
@@ -415,10 +418,9 @@ int autohete_ws_destroy(autohete_ws *ws)
     if (!ws) return AH_EINVAL;
     DeviceGuard g(ws->device);
     (void)hipDeviceSynchronize();
-    for (autohete_ws::Table &t : ws->tables) {
-        if (t.d) (void)hipFree(t.d);
+    for (autohete_ws::Table &t : ws->tables)
         if (t.uploaded) (void)hipEventDestroy(t.uploaded);
-    }
+    if (ws->d_tables) (void)hipFree(ws->d_tables);
     for (int r = 0; r < autohete_ws::kRing; ++r) {
         if (ws->h_stage[r]) (void)hipHostFree(ws->h_stage[r]);
         if (ws->staged[r]) (void)hipEventDestroy(ws->staged[r]);
