@@ -909,3 +909,34 @@ def test_more_chunk_lists_than_cached_tables_and_a_second_stream():
     ref = sum(float(np.sum(oracle.decode(states[i]["grad"], oracle.BF16).astype(np.float64) ** 2)) for i in (3, 5, 8))
     assert abs(got - ref) <= 1e-12 * ref
     ws.close()
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+def test_every_finite_16_bit_gradient_pattern(dtype):
+    """All 65536 bit patterns as gradients (the non-finite ones replaced by zero so that the step
+    is not skipped): subnormals, both zeros, the largest finite values.  The norm of the bf16 set
+    is ~1e39, far beyond fp32, so the clip factor is ~1e-39 and only fp64 keeps it from vanishing."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = oracle.decode(bits, dtype)
+    grad = np.where(np.isfinite(vals), bits, 0).astype(np.uint16)
+    rng = np.random.default_rng(99 + dtype)
+    for hp in (B.hparams(max_grad_norm=1.0), B.hparams(max_grad_norm=0.0, loss_scale=2.0 ** 100 if dtype == B.AH_BF16 else 1024.0)):
+        st = random_state(65536, dtype, rng)
+        st["grad"] = grad.copy()
+        md = ModelData([65536])
+        upload(md, 0, st)
+        ws = B.Workspace(1)
+        gn, gf = run_gpu(md, ws, dtype, 1, hp)
+        on, of = run_oracle([st], dtype, 1, hp)
+        assert gf == of == 0
+        s_gpu = ws.autohete_grad_result_get(stream_handle())[0]
+        ref = float(np.sum((vals[np.isfinite(vals)].astype(np.float64) / hp.loss_scale) ** 2))
+        assert abs(s_gpu - ref) <= 1e-12 * ref                       # fp64 sum of exact squares
+        with np.errstate(over="ignore"):
+            on32 = np.float32(on)
+        if np.isfinite(on32):
+            assert abs(gn - on) <= 1e-5 * on
+        else:
+            assert gn == on32                                        # beyond fp32: both report inf
+        compare_state(download(md, 0), st, "all patterns dtype=%d" % dtype, st["old"])
+        ws.close()
