@@ -89,10 +89,14 @@ typedef struct {
 } autohete_hparams;
 
 /*
- * Workspace: device scratch for the cross-block norm reduction, the 16-byte reduction
- * result, and device copies of the chunk tables.  max_chunks bounds n_chunks of later
- * calls.  Create/destroy allocate/free device memory on the current device and
- * synchronise it; do not call them inside a timed region.
+ * Workspace: device scratch for the cross-block norm reduction, the 32-byte reduction
+ * result, and device copies of the chunk tables of recent calls (up to 32, about 8 MB at most;
+ * found again by content, so a caller that cycles through a few chunk lists uploads each once;
+ * a list is uploaded on the stream of the call that first brings it, and a call that finds it
+ * on another stream waits there for that upload).  max_chunks bounds n_chunks of later calls.
+ * Create/destroy allocate/free device memory on the current device and synchronise it; do not
+ * call them inside a timed region.  One workspace serves one host thread and one stream at a
+ * time: calls on different streams must be ordered by the caller.
  */
 typedef struct autohete_ws autohete_ws;
 int autohete_ws_create(autohete_ws **ws, uint64_t max_chunks);
