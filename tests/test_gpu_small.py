@@ -609,6 +609,22 @@ def test_seventy_thousand_tiny_chunks_cross_the_grid_row_limit():
         a = md.slab[s][dev_idx].cpu().numpy()
         got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
     compare_state(got, flat, "70k chunks", old)
+    # the norm-carrying update over the same 70k rows: its per-wave slots must stay consecutive across launch groups
+    other = B.Workspace(n_chunks)
+    other.autohete_grad_result_set(0.0, 0, stream_handle())
+    ws.autohete_adamw_step_carry(other, md.chunk_array(), n_chunks, B.AH_BF16, 4, hp, stream_handle())
+    torch.cuda.synchronize()
+    carried = other.autohete_grad_result_get(stream_handle())[0]
+    ref = float(np.sum(oracle.decode(flat["grad"], oracle.BF16).astype(np.float64) ** 2))
+    assert abs(carried - ref) <= 1e-12 * ref
+    old = dict(master=flat["master"].copy(), exp_avg=flat["exp_avg"].copy(), exp_avg_sq=flat["exp_avg_sq"].copy())
+    oracle.adamw_chunk(flat["grad"], flat["param_lp"], flat["master"], flat["exp_avg"], flat["exp_avg_sq"], oracle.BF16, 4,
+                       oracle_hp(hp), on, 0)
+    for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):
+        a = md.slab[s][dev_idx].cpu().numpy()
+        got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
+    compare_state(got, flat, "70k chunks, carry", old, drift_steps=1)
+    other.close()
     ws.close()
 
 
