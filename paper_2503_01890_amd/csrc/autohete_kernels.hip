@@ -131,9 +131,21 @@ __device__ __forceinline__ void adamw_elem(float gf, float &p, float &m, float &
         s = __builtin_fma(__builtin_fma(-s, s, vh), hy, s);
         /* 1/den: q from v_rcp_f64, two steps q <- q + q*(1 - den*q). */
         const double den = s + k.eps;
-        double q = __builtin_amdgcn_rcp(den);
+        const double q0 = __builtin_amdgcn_rcp(den);
+        double q = __builtin_fma(q0, __builtin_fma(-den, q0, 1.0), q0);
         q = __builtin_fma(q, __builtin_fma(-den, q, 1.0), q);
-        q = __builtin_fma(q, __builtin_fma(-den, q, 1.0), q);
+        /* The iterations turn three reachable states into NaN where the exact operations do not:
+         * a second moment that overflowed to +inf (a huge but finite gradient, no clipping; then
+         * s = inf * 0), and den = 0 (eps = 0, no second moment yet) or den = +inf.  One class test
+         * per element (den is NaN, +-inf or +-0), and only a wave that sees such an element takes
+         * the branch: there the root of +inf is +inf and the hardware's reciprocal of 0 or inf is
+         * already exact. */
+        const bool odd = __builtin_amdgcn_class(den, 0x267);
+        if (__builtin_amdgcn_ballot_w64(odd) != 0) {
+            asm volatile("" ::: "memory"); /* keeps this a branch: as straight-line selects it costs 0.7 % */
+            const double s_exact = vh < __builtin_huge_val() ? s : vh;
+            q = odd ? __builtin_amdgcn_rcp(s_exact + k.eps) : q;
+        }
         upd = mh * q;
     }
     const double pn = pd - k.lr * (upd + k.wd * pd);

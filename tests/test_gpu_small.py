@@ -956,3 +956,56 @@ def test_every_finite_16_bit_gradient_pattern(dtype):
             assert gn == on32                                        # beyond fp32: both report inf
         compare_state(download(md, 0), st, "all patterns dtype=%d" % dtype, st["old"])
         ws.close()
+
+
+@pytest.mark.parametrize("variant", [B.step_variant(4, 64, 0), B.step_variant(4, 64, 1), B.step_variant(1, 256, 0)])
+def test_degenerate_states_match_the_exact_rule(variant):
+    """States a run can reach without any non-finite gradient: a second moment that overflowed
+    fp32 (huge finite gradient, clipping off), eps = 0 with no second moment yet, a first moment
+    at +-inf.  The fast root / quotient must give what the exact operations give."""
+    inf = np.float32(np.inf)
+    n = 4096
+    rng = np.random.default_rng(3)
+    for eps, clip in ((1e-8, 0.0), (0.0, 0.0), (0.0, 1.0)):
+        st = random_state(n, B.AH_BF16, rng)
+        st["exp_avg_sq"][0::7] = inf                         # overflowed earlier
+        st["exp_avg_sq"][1::7] = 0.0
+        st["grad"][1::7] = 0                                 # v stays 0: denominator is eps alone
+        st["grad"][2::7] = 0x7F7F                            # largest finite bf16: v overflows in this very step
+        st["exp_avg"][3::7] = inf
+        st["exp_avg"][4::7] = -inf
+        st["exp_avg_sq"][4::7] = inf                         # inf / inf
+        st["exp_avg"][5::7] = 0.0
+        st["grad"][5::7] = 0
+        st["exp_avg_sq"][5::7] = 0.0                         # 0 / (0 + eps)
+        hp = B.hparams(eps=eps, max_grad_norm=clip)
+        md = ModelData([n])
+        upload(md, 0, st)
+        ws = B.Workspace(1)
+        ws.tune(B.AH_TUNE_STEP_VARIANT, variant)
+        gn, gf = run_gpu(md, ws, B.AH_BF16, 2, hp)
+        with np.errstate(all="ignore"):
+            on, of = run_oracle([st], B.AH_BF16, 2, hp)
+        assert gf == of == 0
+        got = download(md, 0)
+        for k in ("master", "exp_avg", "exp_avg_sq"):
+            g, o = got[k], st[k]
+            assert np.array_equal(np.isnan(g), np.isnan(o)), (eps, clip, k, "NaN pattern")
+            assert np.array_equal(np.isinf(g), np.isinf(o)) and np.array_equal(np.sign(g[np.isinf(g)]), np.sign(o[np.isinf(o)])), (eps, clip, k, "inf pattern")
+            fin = np.isfinite(o)
+            err = np.abs(g[fin].astype(np.float64) - o[fin].astype(np.float64))
+            tol = 2.0 * np.spacing(np.abs(o[fin]).astype(np.float32)).astype(np.float64)
+            if clip > 0:                                      # the norm (~1e39) is summed in a different order
+                tol = np.maximum(tol, 1e-6 * np.abs(o[fin]))
+            assert (err <= tol).all(), (eps, clip, k, float(err.max()))
+        nan16 = lambda b: (b & 0x7F80) == 0x7F80
+        same = got["param_lp"] == st["param_lp"]
+        both_nan = nan16(got["param_lp"]) & nan16(st["param_lp"]) & ((got["param_lp"] & 0x7F) != 0) & ((st["param_lp"] & 0x7F) != 0)
+        d = np.abs(ordered16_(got["param_lp"]) - ordered16_(st["param_lp"]))
+        assert (same | both_nan | (d <= 1)).all(), (eps, clip, "param_lp")
+        ws.close()
+
+
+def ordered16_(bits):
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
