@@ -143,3 +143,36 @@ def test_host_random_hyperparameters_bit_identical(seed):
                        oracle.hparams(**kw), float(np.sqrt(sumsq)), 0)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes(), (kw, step, k)
+
+
+def test_host_step_degenerate_states(simd):
+    """Overflowed second moment, eps = 0 with no second moment, infinite first moments: the host path
+    uses the exact root and quotient, so even the NaN / inf patterns must equal the oracle's."""
+    n, inf = 4096, np.float32(np.inf)
+    for eps in (1e-8, 0.0):
+        st = make_state(n, B.AH_BF16)
+        st["exp_avg_sq"][0::7] = inf
+        st["exp_avg_sq"][1::7] = 0.0
+        st["grad"][1::7] = 0
+        st["grad"][2::7] = 0x7F7F
+        st["exp_avg"][3::7] = inf
+        st["exp_avg"][4::7] = -inf
+        st["exp_avg_sq"][4::7] = inf
+        st["exp_avg"][5::7] = 0.0
+        st["grad"][5::7] = 0
+        st["exp_avg_sq"][5::7] = 0.0
+        ref = {k: v.copy() for k, v in st.items()}
+        hp, ohp = B.hparams(eps=eps, max_grad_norm=0.0), oracle.hparams(eps=eps, max_grad_norm=0.0)
+        B.autohete_host_adamw_step(host_chunks([st]), 1, B.AH_BF16, 2, hp, 1.0, 0, 3)
+        with np.errstate(all="ignore"):
+            oracle.adamw_chunk(ref["grad"], ref["param_lp"], ref["master"], ref["exp_avg"], ref["exp_avg_sq"],
+                               oracle.BF16, 2, ohp, 1.0, 0)
+        for k in ("master", "exp_avg", "exp_avg_sq"):
+            a, b = st[k], ref[k]
+            assert np.array_equal(np.isnan(a), np.isnan(b)), (eps, k)
+            ok = ~np.isnan(b)
+            assert a[ok].tobytes() == b[ok].tobytes(), (eps, k)
+        nan16 = lambda x: ((x & 0x7F80) == 0x7F80) & ((x & 0x7F) != 0)
+        assert np.array_equal(nan16(st["param_lp"]), nan16(ref["param_lp"]))
+        ok = ~nan16(ref["param_lp"])
+        assert np.array_equal(st["param_lp"][ok], ref["param_lp"][ok])
