@@ -397,3 +397,43 @@ def test_split_path_equals_fused_and_cast_is_library_rne():
         else:
             ref = split["master"].astype(np.float16).view(np.uint16)
         assert np.array_equal(split["param_lp"], ref)
+
+
+def test_limits_at_infinite_second_moment_and_zero_denominator():
+    """Mathematical limits at the corners the update can reach with finite gradients:
+    v = +inf (overflowed earlier) makes the Adam term exactly 0, leaving pure decay;
+    eps = 0 with v = 0 and m != 0 divides by zero: the parameter runs to -+inf with the sign
+    of m; m = v = 0 with eps = 0 is 0/0 (NaN).  The largest finite bf16 gradient overflows v in
+    the step itself while the parameter stays finite (its own update still sees a finite v_hat
+    only if fp64 holds it: 1e77 does)."""
+    n = 64
+    st = state(n, BF16)
+    p0 = st["master"].astype(np.float64)
+    st["exp_avg_sq"][:] = np.inf
+    hp = oracle.hparams(lr=0.125, weight_decay=0.5, max_grad_norm=0.0)   # lr*wd = 1/16 exactly
+    g = lowp(RNG.normal(0, 1e-3, n), BF16)
+    oracle.adamw_chunk(g, st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], BF16, 3, hp, 0.0, 0)
+    assert np.array_equal(st["master"], (p0 * (1 - 0.0625)).astype(np.float32))
+    assert np.isinf(st["exp_avg_sq"]).all() and np.isfinite(st["exp_avg"]).all()
+
+    st = state(n, BF16, zero_moments=True)
+    st["exp_avg"][: n // 2] = 1e-3
+    st["exp_avg"][n // 2:] = -1e-3
+    st["exp_avg"][0] = 0.0
+    hp0 = oracle.hparams(eps=0.0, weight_decay=0.0, max_grad_norm=0.0)
+    with np.errstate(all="ignore"):
+        oracle.adamw_chunk(np.zeros(n, np.uint16), st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"],
+                           BF16, 2, hp0, 0.0, 0)
+    assert np.isnan(st["master"][0])
+    assert (st["master"][1: n // 2] == -np.inf).all() and (st["master"][n // 2:] == np.inf).all()
+
+    st = state(n, BF16, zero_moments=True)
+    p0 = st["master"].astype(np.float64)
+    big = np.full(n, 0x7F7F, np.uint16)                                   # 3.39e38, finite
+    hp1 = oracle.hparams(lr=1e-3, weight_decay=0.0, max_grad_norm=0.0)
+    with np.errstate(all="ignore"):
+        oracle.adamw_chunk(big, st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], BF16, 1, hp1, 0.0, 0)
+    assert np.isinf(st["exp_avg_sq"]).all()                               # 1e-3 * 1.15e77 does not fit fp32
+    # step 1: m_hat = g, v_hat = g^2 in fp64 -> update = lr * g / (|g| + eps) = lr to within eps/|g|
+    want = p0 - float(np.float32(1e-3))
+    assert (np.abs(st["master"].astype(np.float64) - want) <= ulp32(want)).all()
