@@ -90,7 +90,7 @@ typedef struct {
 
 /*
  * Workspace: device scratch for the cross-block norm reduction, the 32-byte reduction
- * result, and device copies of the chunk tables of recent calls (up to 32, about 8 MB at most;
+ * result, and device copies of the chunk tables of recent calls (up to 128, about 8 MB at most;
  * found again by content, so a caller that cycles through a few chunk lists uploads each once;
  * a list is uploaded on the stream of the call that first brings it, and a call that finds it
  * on another stream waits there for that upload).  max_chunks bounds n_chunks of later calls.

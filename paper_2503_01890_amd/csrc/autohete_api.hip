@@ -376,8 +376,10 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
     ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
     bool ok = true;
     const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
-    /* as many cached tables and staging buffers as fit a few MB, at least the two a prep + step pair needs */
-    const size_t n_tables = std::min<size_t>(32, std::max<size_t>(2, (8u << 20) / tab_bytes));
+    /* As many cached tables and staging buffers as fit a few MB, at least the two a prep + step pair
+     * needs.  128 covers one table per transformer block and kernel for models of up to ~60 blocks; a
+     * caller cycling through more lists than there are entries misses every time (least recently used). */
+    const size_t n_tables = std::min<size_t>(128, std::max<size_t>(2, (8u << 20) / tab_bytes));
     ws->ring_depth = (int)std::min<size_t>(autohete_ws::kRing, std::max<size_t>(1, (4u << 20) / tab_bytes));
     try {
         ws->tables.resize(n_tables);

@@ -893,11 +893,12 @@ def test_nothing_is_written_outside_the_chunks(variant):
 
 
 def test_more_chunk_lists_than_cached_tables_and_a_second_stream():
-    """Chunk tables are kept on the device by content and replaced least-recently-used.  Forty
-    single-chunk lists, cycled three times, overflow that cache; every call must still see its own
-    list.  A list first used on one stream and at once on another must be complete there too."""
+    """Chunk tables are kept on the device by content and replaced least-recently-used.  A hundred
+    single-chunk lists (two tables each), cycled three times, overflow that cache of 128; every call
+    must still see its own list.  A list first used on one stream and at once on another must be
+    complete there too."""
     rng = np.random.default_rng(808)
-    numels = [int(x) for x in rng.integers(100, 30_000, 40)]
+    numels = [int(x) for x in rng.integers(100, 30_000, 100)]
     states = [random_state(n, B.AH_BF16, rng) for n in numels]
     md = ModelData(numels)
     for i, st in enumerate(states):
@@ -906,7 +907,7 @@ def test_more_chunk_lists_than_cached_tables_and_a_second_stream():
     hp = B.hparams(max_grad_norm=0.01)
     s = stream_handle()
     for step in (1, 2, 3):
-        for i in range(40):
+        for i in range(100):
             arr = md.chunk_array([i])
             ws.autohete_grad_prep(arr, 1, B.AH_BF16, 1.0, 0.0, s)
             ws.autohete_adamw_step(arr, 1, B.AH_BF16, step, hp, s)
