@@ -1,17 +1,21 @@
 /*
- * autohete_kernels.hip -- the two streaming kernels of the chunked mixed-precision AdamW
- * update for gfx950 (MI355X), and their launchers.
+ * autohete_kernels.hip -- the streaming kernels of the chunked mixed-precision AdamW update for
+ * gfx950 (MI355X), and their launchers.
  *
- *   grad_prep_kernel   2 B/element read.   Sum of squares of the raw 16-bit gradients in
- *                      fp64 (per lane -> wavefront shuffle -> LDS -> one partial per block ->
- *                      ticket counter; the last block to arrive folds the partials in index
- *                      order), finite check, loss-scale removal on the scalar result.
- *   adamw_step_kernel  14 B/element read + 14 B/element written.  Fused unscale, clip,
- *                      moments, bias correction, decoupled decay, fp32 and 16-bit write-back.
+ *   grad_prep_kernel         2 B/element read.  Sum of squares of the raw 16-bit gradients in
+ *                            fp64 (per lane -> wavefront shuffle -> LDS -> one partial per block ->
+ *                            ticket counter; the last block to arrive folds the partials in index
+ *                            order), finite check, loss-scale removal on the scalar result.
+ *   adamw_step_kernel        14 B/element read + 14 B/element written.  Fused unscale, clip,
+ *                            moments, bias correction, decoupled decay, fp32 and 16-bit write-back
+ *                            (or without the 16-bit write-back: 26 B/element).
+ *   cast_params_kernel       4 B read + 2 B written: 16-bit parameters from the fp32 copy on demand.
+ *   adamw_step_carry_kernel  the update plus the squares of the gradients it reads, for the norm of
+ *                            the next iteration (per-block stepping); fold_partials_kernel sums them.
  *
- * Both are HBM-bound (about 0.7 flop/byte), so there is no MFMA here: the design goal is
- * that every byte moves once, in full-width coalesced vector accesses, with enough loads in
- * flight per CU.  Model data layout: section 2.1 of the paper (16-bit parameters and
+ * All are HBM-bound (about 0.7 flop/byte), so there is no MFMA here: the design goal is that
+ * every byte moves once, in full-width coalesced vector accesses, with the right amount of loads
+ * in flight per CU.  Model data layout: section 2.1 of the paper (16-bit parameters and
  * gradients, fp32 momentum / variance / parameter copy).  The arithmetic of the update is
  * kept in fp64 (full rate on CDNA, hidden under the memory time) so that stored values are
  * the correctly rounded results of the rule stated in autohete.h.
