@@ -64,18 +64,20 @@ __device__ __forceinline__ void st(AH_GLOBAL T *p, T v)
  * pattern, stores with sc1+nt are ~1 % faster than nt alone (and nt alone ~13 % faster than
  * plain stores when the loads are nt); the load policy makes no difference beyond nt.  The
  * compiler has no builtin for this combination on vector types, hence the inline assembly; the
- * stored lines are never read again by this kernel, so no wait is needed after them.  The
- * trailing s_nop supplies, by hand, the one wait state the ISA requires between a VMEM store of
- * more than 64 bits and a VALU write to its data registers: the compiler inserts it for its own
- * stores but cannot see into an asm statement. */
+ * stored lines are never read again by this kernel, so no wait is needed after them.
+ * The trailing s_nop supplies, by hand, the wait states the ISA requires between a VMEM store of
+ * more than 64 bits and a VALU write to its data registers: the compiler inserts them for its own
+ * stores but cannot see into an asm statement.  gfx940 and later need TWO wait states there
+ * ("s_nop 1"); with one, a wave now and then stored a later value of the register instead --
+ * seen as a 16-bit intermediate of the parameter packing in 16 elements of the first moment. */
 template <typename T>
 __device__ __forceinline__ void st_stream(AH_GLOBAL T *p, T v)
 {
     static_assert(sizeof(T) == 16 || sizeof(T) == 8 || sizeof(T) == 4 || sizeof(T) == 2, "store width");
-    if constexpr (sizeof(T) == 16) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
-    else if constexpr (sizeof(T) == 8) asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
-    else if constexpr (sizeof(T) == 4) asm volatile("global_store_dword %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
-    else asm volatile("global_store_short %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"((uint32_t)v) : "memory");
+    if constexpr (sizeof(T) == 16) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+    else if constexpr (sizeof(T) == 8) asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+    else if constexpr (sizeof(T) == 4) asm volatile("global_store_dword %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+    else asm volatile("global_store_short %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"((uint32_t)v) : "memory");
 }
 
 /* 16-bit <-> fp32.  bf16 is the upper half of an fp32 word; fp16 uses the hardware converts.
