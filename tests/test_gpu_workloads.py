@@ -240,7 +240,7 @@ def test_workload(name, it):
         torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name,iterations", [("gpt-1.3b", 12), ("ragged-fp16", 6)])
+@pytest.mark.parametrize("name,iterations", [("gpt-1.3b", 12), ("ragged-fp16", 6), ("gpt-6.7b", 3)])
 def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iterations):
     """Whole-model, every byte: three copies of the model data (bf16, 1.3B parameters; fp16, 2.7B) are stepped with the
     same gradients by differently compiled kernels -- the default update (4 elements per lane, one
@@ -255,7 +255,9 @@ def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iteratio
     torch.cuda.empty_cache()
     w = synthdata.workload(name)
     C, n = w.chunk_elems, w.n_chunks
-    copies = [ModelData([C] * n) for _ in range(3)]
+    # the headline model fits twice, not three times: there the norm-carrying copy is left out
+    n_copies = 3 if 3 * 16 * C * n < 0.8 * torch.cuda.get_device_properties(0).total_memory else 2
+    copies = [ModelData([C] * n) for _ in range(n_copies)]
     for md in copies:
         for c in range(n):
             fill_device_chunk(md, w, c)
@@ -276,14 +278,19 @@ def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iteratio
             ws[k].autohete_adamw_step(arrs[k], n, w.dtype, it, hp, s)
         sumsq, _, flag = ws[0].autohete_grad_result_get(s)
         assert flag == 0 and ws[1].autohete_grad_result_get(s)[0] == sumsq
-        ws[2].autohete_grad_result_set(sumsq, 0, s)
-        carried.autohete_grad_result_set(0.0, 0, s)
-        ws[2].autohete_adamw_step_carry(carried, arrs[2], n, w.dtype, it, hp, s)
+        if n_copies == 3:
+            ws[2].autohete_grad_result_set(sumsq, 0, s)
+            carried.autohete_grad_result_set(0.0, 0, s)
+            ws[2].autohete_adamw_step_carry(carried, arrs[2], n, w.dtype, it, hp, s)
+            torch.cuda.synchronize()
+            assert abs(carried.autohete_grad_result_get(s)[0] - sumsq) <= 1e-12 * sumsq
         torch.cuda.synchronize()
-        assert abs(carried.autohete_grad_result_get(s)[0] - sumsq) <= 1e-12 * sumsq
         ref = copies[0].storages()[0]
-        for k in (1, 2):
-            assert torch.equal(ref, copies[k].storages()[0]), "iteration %d: copy %d differs from the default kernel's" % (it, k)
+        for k in range(1, n_copies):
+            other = copies[k].storages()[0]
+            for a in range(0, ref.numel(), 1 << 30):          # in slices: the comparison allocates a result of its own
+                assert torch.equal(ref[a:a + (1 << 30)], other[a:a + (1 << 30)]), \
+                    "iteration %d: copy %d differs from the default kernel's in GiB %d" % (it, k, a >> 30)
     for x in ws + [carried]:
         x.close()
     del copies
