@@ -244,8 +244,8 @@ def test_workload(name, it):
 def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iterations):
     """Whole-model, every byte: three copies of the model data (bf16, 1.3B parameters; fp16, 2.7B) are stepped with the
     same gradients by differently compiled kernels -- the default update (4 elements per lane, one
-    wave per block), the 2-elements-per-lane / 128-thread variant, and the norm-carrying update --
-    for a dozen iterations.  All three perform the same operations per element, so every stored
+    wave per block); every other lane / block shape of the fast mode in turn; and alternately the
+    norm-carrying update and the update without write-back followed by the cast.  All three perform the same operations per element, so every stored
     byte must be identical after every iteration.  An instruction-scheduling or data-hazard fault in
     one compiled variant (rare, per wave) shows up here, where the sampled-chunk comparison with the
     oracle could miss it: about 2 * 10^8 wave-tiles are compared."""
@@ -263,7 +263,7 @@ def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iteratio
             fill_device_chunk(md, w, c)
     s = stream_handle()
     ws = [B.Workspace(n) for _ in range(3)]
-    ws[1].tune(B.AH_TUNE_STEP_VARIANT, B.step_variant(2, 128, 0))
+    others = [(2, 128), (4, 128), (4, 256), (2, 64), (2, 256), (1, 128), (1, 256), (1, 512)]   # copy 1 cycles through them
     carried = B.Workspace(n)
     hp = B.hparams(**w.hparams, loss_scale=w.loss_scale)
     arrs = [md.chunk_array() for md in copies]
@@ -273,17 +273,22 @@ def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iteratio
         for md in copies[1:]:
             for c in range(n):
                 md.view("grad", c).copy_(copies[0].view("grad", c))
+        ws[1].tune(B.AH_TUNE_STEP_VARIANT, B.step_variant(*others[(it - 1) % len(others)], 0))
         for k in (0, 1):
             ws[k].autohete_grad_prep(arrs[k], n, w.dtype, w.loss_scale, 0.0, s)
             ws[k].autohete_adamw_step(arrs[k], n, w.dtype, it, hp, s)
         sumsq, _, flag = ws[0].autohete_grad_result_get(s)
         assert flag == 0 and ws[1].autohete_grad_result_get(s)[0] == sumsq
-        if n_copies == 3:
+        if n_copies == 3 and it % 2:
             ws[2].autohete_grad_result_set(sumsq, 0, s)
             carried.autohete_grad_result_set(0.0, 0, s)
             ws[2].autohete_adamw_step_carry(carried, arrs[2], n, w.dtype, it, hp, s)
             torch.cuda.synchronize()
             assert abs(carried.autohete_grad_result_get(s)[0] - sumsq) <= 1e-12 * sumsq
+        elif n_copies == 3:                       # even iterations: update without write-back, then the cast
+            ws[2].autohete_grad_result_set(sumsq, 0, s)
+            ws[2].autohete_adamw_step_master(arrs[2], n, w.dtype, it, hp, s)
+            ws[2].autohete_cast_params(arrs[2], n, w.dtype, s)
         torch.cuda.synchronize()
         ref = copies[0].storages()[0]
         for k in range(1, n_copies):
