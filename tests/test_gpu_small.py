@@ -1010,3 +1010,48 @@ def test_degenerate_states_match_the_exact_rule(variant):
 def ordered16_(bits):
     b = bits.astype(np.int32)
     return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+def test_exact_mode_is_bit_identical_to_the_oracle_given_the_same_norm(dtype):
+    """MODE 1 of the update kernel uses correctly rounded fp64 root and divisions in the oracle's
+    operation order, so with the same S handed to both sides every stored bit must agree -- four
+    million elements, three steps, no tolerance.  The fast mode (Newton iterations) is then held
+    against it: it may differ from the exact mode in the last bit of a vanishing fraction only."""
+    n = 1 << 22
+    rng = np.random.default_rng(2024 + dtype)
+    scale = 1.0 if dtype == B.AH_BF16 else 128.0
+    st = random_state(n, dtype, rng, scale=scale)
+    exact, fast = ModelData([n]), ModelData([n])
+    upload(exact, 0, st)
+    upload(fast, 0, st)
+    ws_e, ws_f = B.Workspace(1), B.Workspace(1)
+    ws_e.tune(B.AH_TUNE_STEP_VARIANT, B.step_variant(4, 64, 1))
+    hp = B.hparams(max_grad_norm=0.5, loss_scale=scale)
+    s = stream_handle()
+    for step in (1, 2, 3):
+        if step > 1:
+            st["grad"] = random_state(n, dtype, rng, scale=scale)["grad"]
+            upload(exact, 0, dict(grad=st["grad"]))
+            upload(fast, 0, dict(grad=st["grad"]))
+        sumsq, flag = oracle.grad_accumulate(st["grad"], dtype, scale)
+        assert flag == 0
+        norm = float(np.sqrt(sumsq))
+        for ws, md in ((ws_e, exact), (ws_f, fast)):
+            ws.autohete_grad_result_set(sumsq, 0, s)
+            ws.autohete_adamw_step(md.chunk_array(), 1, dtype, step, hp, s)
+        torch.cuda.synchronize()
+        oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], dtype, step,
+                           oracle_hp(hp), norm, 0)
+        got_e, got_f = download(exact, 0), download(fast, 0)
+        for k in ("master", "exp_avg", "exp_avg_sq", "param_lp"):
+            assert got_e[k].tobytes() == st[k].tobytes(), (step, k, "exact mode differs from the oracle")
+        for k in ("master", "exp_avg", "exp_avg_sq"):
+            diff = got_f[k].view(np.uint32) != st[k].view(np.uint32)
+            assert diff.sum() <= 1e-5 * n, (step, k, int(diff.sum()))
+            d = np.abs(got_f[k].view(np.int32).astype(np.int64) - st[k].view(np.int32).astype(np.int64))
+            assert d.max() <= 1, (step, k, "fast mode more than one ulp from the exact result")
+        assert (got_f["param_lp"] != st["param_lp"]).sum() <= 1e-6 * n
+        upload(fast, 0, st)                                  # both continue from the oracle's state
+    ws_e.close()
+    ws_f.close()
