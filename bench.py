@@ -209,8 +209,10 @@ def main():
     assert flag == 0, "synthetic gradients must be finite"
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    prep_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    step_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    prep_all = sorted(e[0].elapsed_time(e[1]) for e in events)
+    step_all = sorted(e[1].elapsed_time(e[2]) for e in events)
+    prep_ms, step_ms = sum(prep_all) / args.steps, sum(step_all) / args.steps
+    median = lambda xs: 0.5 * (xs[(len(xs) - 1) // 2] + xs[len(xs) // 2])
     step_bytes = 26 if split else STEP_BYTES_PER_ELEM        # no 16-bit write-back in the split path
     total_bytes = step_bytes + PREP_BYTES_PER_ELEM + (6 if split else 0)
     step_gbps = step_bytes * elems / step_ms / 1e6
@@ -238,9 +240,10 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": step_gbps / HBM_PEAK_GBPS,
                      "traffic": None if split else measured_traffic(w.name),
                      "algorithmic_bytes_per_launch": step_bytes * elems,
-                     "avg_launch_ms": step_ms},
+                     "avg_launch_ms": step_ms, "median_launch_ms": median(step_all), "min_launch_ms": step_all[0]},
         "prep_kernel": {"kernel": "grad_prep_kernel", "achieved": prep_gbps, "unit": "GB/s",
-                        "frac": prep_gbps / HBM_PEAK_GBPS, "avg_launch_ms": prep_ms},
+                        "frac": prep_gbps / HBM_PEAK_GBPS, "avg_launch_ms": prep_ms, "median_launch_ms": median(prep_all),
+                        "min_launch_ms": prep_all[0]},
     }
     if split:
         cast_ms = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
