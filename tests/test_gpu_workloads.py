@@ -3,8 +3,9 @@ bench.py times (library defaults).  The model data is generated on the device by
 of the seeded generator; the oracle regenerates what it needs on the CPU from the same seeds:
   - the global gradient norm / skip flag of EVERY iteration, over every resident chunk
     (plus, for the half-resident workload, the host-side partial sum);
-  - full element-by-element state of a sample of chunks (first, last/padded, tensor-boundary
-    holders, seeded random ones), replayed through every iteration.  After each iteration's
+  - full element-by-element state of every chunk (124M and 1.3B configurations) or of a sample
+    of 16 to 32 chunks (first, last/padded, tensor-boundary holders, seeded random ones),
+    replayed through every iteration.  After each iteration's
     comparison the ORACLE's state of those chunks is uploaded over the device's, so that every
     step is judged from identical inputs (data flows oracle -> device only, never back);
     one sampled chunk is left free-running and judged with the drift allowance instead.
@@ -26,7 +27,8 @@ from paper_2503_01890_amd.modeldata import ModelData, STREAMS
 
 pytestmark = pytest.mark.gpu
 
-SAMPLES = {"gpt-124m": None, "gpt-1.3b": 6, "gpt-6.7b": 4, "gpt-13b-half-resident": 4, "ragged-fp16": 5}
+# chunks replayed by the oracle element by element (None = every chunk of the workload)
+SAMPLES = {"gpt-124m": None, "gpt-1.3b": None, "gpt-6.7b": 16, "gpt-13b-half-resident": 16, "ragged-fp16": 32}
 BAD_BITS = {(synthdata.FP16, "inf"): 0x7C00, (synthdata.FP16, "nan"): 0x7E00,
             (synthdata.BF16, "inf"): 0x7F80, (synthdata.BF16, "nan"): 0x7FC0}
 
@@ -79,7 +81,8 @@ class Run:
             while len(set(picks)) < k:
                 picks.append(int(rng.integers(0, w.n_resident)))
             self.sample = sorted(set(picks))
-        self.host = {c: cpu_chunk_state(w, c) for c in self.sample}
+        with cf.ThreadPoolExecutor(N_THREADS) as ex:
+            self.host = dict(zip(self.sample, ex.map(lambda c: cpu_chunk_state(w, c), self.sample)))
         # one sampled chunk (not the first or last) is never re-synchronised: it drifts freely
         mid = [c for c in self.sample if c not in (0, w.n_resident - 1)]
         self.free = mid[len(mid) // 2] if (mid and w.steps > 1) else None
@@ -137,7 +140,8 @@ class Run:
             assert self.checksums() == before, "a skipped step must leave every stream bit-identical"
         else:
             assert abs(gn - on) <= 1e-5 * on, (it, gn, on)
-        def oracle_step(c):          # runs in a worker thread; the C calls release the GIL
+        def oracle_step(c):          # oracle update of one chunk, then its comparison with the device's;
+                                     # runs in a worker thread (the C calls and numpy release the GIL)
             g = cpu_chunk_grad(w, c, it, scale)
             for (pc, pi), bits in patch.items():
                 if pc == c:
@@ -155,20 +159,19 @@ class Run:
             else:
                 oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
                                    oracle_hp(hp), on, of)
-            return old
-
-        with cf.ThreadPoolExecutor(min(N_THREADS, len(self.sample))) as ex:
-            olds = dict(zip(self.sample, ex.map(oracle_step, self.sample)))
-        for c in self.sample:
-            h, old = self.host[c], olds.pop(c)
             got = download(md, c, ("param_lp", "master", "exp_avg", "exp_avg_sq"))
             st = compare_state(got, h, "%s it=%d chunk=%d" % (w.name, it, c), old,
                                drift_steps=(self.t - 1 if c == self.free else 0))
             st.update(it=it, chunk=c)
+            return st
+
+        with cf.ThreadPoolExecutor(min(N_THREADS, len(self.sample))) as ex:
+            results = list(ex.map(oracle_step, self.sample))       # a failed comparison is raised here
+        for c, st in zip(self.sample, results):
             self.stats.append(st)
             if c != self.free and not of and any(st[k] for k in ("master_mismatch", "exp_avg_mismatch",
                                                                   "exp_avg_sq_mismatch", "param_lp_mismatch")):
-                upload(md, c, h)                     # oracle -> device: next step starts identical
+                upload(md, c, self.host[c])          # oracle -> device: next step starts identical
         if of:
             self.scale = scale / 2.0
         else:
