@@ -45,7 +45,8 @@ enum {
     AH_EALIGN = -2, /* a device pointer is not 16-byte aligned */
     AH_ENOMEM = -3, /* allocation failed, or more chunks than the workspace was made for */
     AH_EHIP = -4,   /* a HIP runtime call failed */
-    AH_EINFEASIBLE = -5 /* autohete_strategy_search: no strategy satisfies the memory constraints */
+    AH_EINFEASIBLE = -5, /* autohete_strategy_search: no strategy satisfies the memory constraints */
+    AH_ELIMIT = -6  /* autohete_grad_prep_static: more chunks than AUTOHETE_STATIC_MAX_CHUNKS */
 };
 
 enum { AH_BF16 = 0, AH_FP16 = 1 }; /* format of the two 16-bit streams */
@@ -134,6 +135,34 @@ int autohete_grad_prep(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
  */
 int autohete_grad_prep_accumulate(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n_chunks,
                                   int lowp_dtype, float loss_scale, void *stream);
+
+/*
+ * autohete_grad_prep for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It needs no workspace and makes no allocation (no
+ * hipMalloc, hipFree, host-pinned memory or upload): the chunk list travels in the kernel
+ * arguments, and the cross-block scratch of the reduction (2048 fp64 block partials and a ticket
+ * word, 16640 bytes) is a static device array inside the library, one copy per GPU, held until the
+ * process ends.  Same kernel body, grid and summation order as autohete_grad_prep with default
+ * tuning, so S is bit-identical to that call's on the same chunk list.
+ *   chunks      host in : n_chunks descriptors; only .grad (device, 16-byte aligned) and .numel used.
+ *                         A descriptor may span several chunks that are contiguous in memory.
+ *   n_chunks    0..AUTOHETE_STATIC_MAX_CHUNKS (0: S = extra_sumsq); more -> AH_ELIMIT, nothing runs
+ *   result      DEVICE out, caller-owned, 8-byte aligned: {S, sqrt(S), (float)sqrt(S), skip flag},
+ *               written on `stream`; sqrt(S) is NaN when the flag is set
+ * The device current at the call is used; the pointers must belong to it.  Every call on a GPU
+ * shares that GPU's scratch array: calls that overlap on one GPU (different streams, or threads)
+ * race -- order them.  The ticket word is cleared by a small kernel ahead of the pass (no memset
+ * node), so the call may be captured.  Errors: AH_EINVAL, AH_EALIGN, AH_ELIMIT, AH_EHIP.
+ */
+#define AUTOHETE_STATIC_MAX_CHUNKS 128
+typedef struct {
+    double sumsq;       /* S = extra_sumsq + sum (grad / loss_scale)^2 */
+    double norm_d;      /* sqrt(S); NaN when found_inf */
+    float norm;         /* the same, rounded to fp32 */
+    uint32_t found_inf; /* 1: a gradient or S is not finite -- skip the step */
+} autohete_grad_result;
+int autohete_grad_prep_static(const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype, float loss_scale,
+                              double extra_sumsq, void *stream, autohete_grad_result *result);
 
 /*
  * The update (rule at the top of this file) over the given chunks in one fused pass:

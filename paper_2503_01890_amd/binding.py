@@ -10,7 +10,8 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libautohete.so")
 
-AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP, AH_EINFEASIBLE = 0, -1, -2, -3, -4, -5
+AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP, AH_EINFEASIBLE, AH_ELIMIT = 0, -1, -2, -3, -4, -5, -6
+AUTOHETE_STATIC_MAX_CHUNKS = 128
 AH_BF16, AH_FP16 = 0, 1
 AH_TUNE_STEP_BLOCKS_PER_CU, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT, AH_TUNE_CAST_BLOCKS_PER_CU = 0, 1, 2, 3
 
@@ -42,6 +43,11 @@ class autohete_chunk(ctypes.Structure):
 class autohete_hparams(ctypes.Structure):
     _fields_ = [(k, ctypes.c_float) for k in
                 ("lr", "beta1", "beta2", "eps", "weight_decay", "max_grad_norm", "loss_scale")]
+
+
+class autohete_grad_result(ctypes.Structure):
+    _fields_ = [("sumsq", ctypes.c_double), ("norm_d", ctypes.c_double), ("norm", ctypes.c_float),
+                ("found_inf", ctypes.c_uint32)]
 
 
 class autohete_cost_model(ctypes.Structure):
@@ -80,6 +86,9 @@ _lib.autohete_grad_prep.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chu
 _lib.autohete_grad_prep_accumulate.restype = ctypes.c_int
 _lib.autohete_grad_prep_accumulate.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64,
                                                ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+_lib.autohete_grad_prep_static.restype = ctypes.c_int
+_lib.autohete_grad_prep_static.argtypes = [ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int, ctypes.c_float,
+                                           ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
 _lib.autohete_adamw_step.restype = ctypes.c_int
 _lib.autohete_adamw_step.argtypes = [ctypes.c_void_p, ctypes.POINTER(autohete_chunk), ctypes.c_uint64, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.POINTER(autohete_hparams), ctypes.c_void_p]
@@ -132,6 +141,14 @@ def autohete_chunk_layout(tensor_numel, chunk_elems):
     _check(_lib.autohete_chunk_layout(numel, n, int(chunk_elems), off, ctypes.byref(nc), ctypes.byref(tot),
                                       ctypes.byref(pad)), "autohete_chunk_layout")
     return list(off[:n]), nc.value, tot.value, pad.value
+
+
+def autohete_grad_prep_static(chunks, n_chunks, lowp_dtype, loss_scale, extra_sumsq, stream, result_dev_ptr):
+    """The workspace-free, allocation-free norm pass; result_dev_ptr: device address of 32 bytes
+    (an autohete_grad_result) that the kernel fills on `stream`."""
+    _check(_lib.autohete_grad_prep_static(chunks, n_chunks, lowp_dtype, loss_scale, extra_sumsq,
+                                          ctypes.c_void_p(stream), ctypes.c_void_p(result_dev_ptr)),
+           "autohete_grad_prep_static")
 
 
 def autohete_strategy_eval(model, n_ckpt, n_param_offload, n_optim_offload):

@@ -337,6 +337,7 @@ const char *autohete_strerror(int status)
         case AH_ENOMEM: return "out of memory or more chunks than the workspace holds";
         case AH_EHIP: return "HIP runtime error";
         case AH_EINFEASIBLE: return "no strategy satisfies the memory constraints";
+        case AH_ELIMIT: return "more chunks than the allocation-free entry point takes";
         default: return "unknown status";
     }
 }
@@ -522,6 +523,38 @@ int autohete_grad_prep_accumulate(autohete_ws *ws, const autohete_chunk *chunks,
                                   int lowp_dtype, float loss_scale, void *stream)
 {
     return prep_common(ws, chunks, n_chunks, lowp_dtype, loss_scale, 0.0, true, stream, nullptr, nullptr);
+}
+
+int autohete_grad_prep_static(const autohete_chunk *chunks, uint64_t n_chunks, int lowp_dtype, float loss_scale,
+                              double extra_sumsq, void *stream, autohete_grad_result *result)
+{
+    static_assert(sizeof(autohete_grad_result) == sizeof(GradResult), "the public result is the kernels' result");
+    static_assert(AUTOHETE_STATIC_MAX_CHUNKS == ah::kStaticMaxChunks, "header and kernels agree on the limit");
+    if (lowp_dtype != AH_BF16 && lowp_dtype != AH_FP16) return AH_EINVAL;
+    if (!(loss_scale > 0.0f) || !isfinite(loss_scale)) return AH_EINVAL;
+    if (!result || (n_chunks && !chunks)) return AH_EINVAL;
+    if (reinterpret_cast<uintptr_t>(result) & 7u) return AH_EALIGN;
+    if (n_chunks > (uint64_t)ah::kStaticMaxChunks) return AH_ELIMIT;
+    ah::PrepRows rows; /* on the stack: copied into the launch's argument buffer by the runtime */
+    const uint32_t tile_elems = ah::prep_tile_elems();
+    uint64_t tiles = 0;
+    for (uint64_t i = 0; i < n_chunks; ++i) {
+        int rc = validate_chunk(chunks[i], kGrad);
+        if (rc != AH_OK) return rc;
+        rows.grad[i] = static_cast<const uint16_t *>(chunks[i].grad);
+        rows.numel[i] = chunks[i].numel;
+        rows.tile_begin[i] = tiles;
+        tiles += (chunks[i].numel + tile_elems - 1) / tile_elems;
+    }
+    for (uint64_t i = n_chunks; i <= (uint64_t)ah::kStaticMaxChunks; ++i) { /* sentinel, and defined values beyond */
+        rows.grad[i] = nullptr;
+        rows.numel[i] = 0;
+        rows.tile_begin[i] = tiles;
+    }
+    return ah::launch_prep_static(lowp_dtype, static_cast<hipStream_t>(stream), rows, tiles,
+                                  1.0 / (double)loss_scale, extra_sumsq,
+                                  reinterpret_cast<GradResult *>(result)) == hipSuccess
+               ? AH_OK : AH_EHIP;
 }
 
 /* carry_to != NULL: the norm-carrying update; the squares of these chunks' gradients are folded

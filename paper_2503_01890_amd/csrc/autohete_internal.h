@@ -69,6 +69,22 @@ hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const Dev
                        uint32_t *ticket, GradResult *res);
 hipError_t launch_set_result(hipStream_t stream, GradResult *res, double sumsq, uint32_t found_inf);
 
+/* Chunk list of the allocation-free norm pass, passed by value in the kernel arguments (3096 of the
+ * 4096 bytes a launch may carry); entry n is the sentinel holding the total tile count. */
+constexpr int kStaticMaxChunks = 128;
+struct PrepRows {
+    const uint16_t *grad[kStaticMaxChunks + 1];
+    uint64_t numel[kStaticMaxChunks + 1];
+    uint64_t tile_begin[kStaticMaxChunks + 1];
+};
+/* Cross-block scratch of that pass, a file-scope device array: block partials, then the ticket. */
+constexpr int kStaticMaxBlocks = 2048;
+constexpr size_t kStaticScratchBytes = kStaticMaxBlocks * sizeof(double) + 256;
+/* Norm pass over `rows` on the current device with the static scratch; the 32-byte result goes to
+ * res (device memory of the caller).  Makes no allocation. */
+hipError_t launch_prep_static(int dtype, hipStream_t stream, const PrepRows &rows, uint64_t total_tiles,
+                              double inv_scale, double extra_sumsq, GradResult *res);
+
 constexpr int kPrepUnroll = 8; /* 8 x 16 B per lane in flight: 32 KB per 256-thread block */
 inline uint32_t prep_tile_elems() { return (uint32_t)(kThreads * kPrepVec * kPrepUnroll); }
 

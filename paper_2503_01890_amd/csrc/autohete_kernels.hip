@@ -20,6 +20,9 @@
  * kept in fp64 (full rate on CDNA, hidden under the memory time) so that stored values are
  * the correctly rounded results of the rule stated in autohete.h.
  */
+#include <algorithm>
+#include <mutex>
+
 #include "autohete_internal.h"
 
 namespace ah {
@@ -443,10 +446,26 @@ __device__ __forceinline__ void publish_total(GradResult *res, double raw_sum, d
     res->found_inf = bad ? 1u : 0u;
 }
 
-template <int DT>
-__global__ void __launch_bounds__(kThreads)
-grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t total_tiles, double inv_scale,
-                 double extra_sumsq, uint32_t accumulate, double *partials, uint32_t *ticket, GradResult *res)
+/* Where the norm pass finds its chunk list: rows of the table in device memory (the workspace's
+ * copy), or rows passed by value in the kernel arguments (the allocation-free entry point; read
+ * through the scalar unit either way).  Row n_chunks is the sentinel. */
+struct TableInMemory {
+    const DevChunk *__restrict__ rows;
+    __device__ __forceinline__ const uint16_t *grad(uint32_t c) const { return rows[c].grad; }
+    __device__ __forceinline__ uint64_t numel(uint32_t c) const { return rows[c].numel; }
+    __device__ __forceinline__ uint64_t tile_begin(uint32_t c) const { return rows[c].tile_begin; }
+};
+struct TableInArgs {
+    const PrepRows &r;
+    __device__ __forceinline__ const uint16_t *grad(uint32_t c) const { return r.grad[c]; }
+    __device__ __forceinline__ uint64_t numel(uint32_t c) const { return r.numel[c]; }
+    __device__ __forceinline__ uint64_t tile_begin(uint32_t c) const { return r.tile_begin[c]; }
+};
+
+template <int DT, typename Table>
+__device__ __forceinline__ void
+grad_prep_body(const Table tab, uint64_t total_tiles, double inv_scale, double extra_sumsq, uint32_t accumulate,
+               double *partials, uint32_t *ticket, GradResult *res)
 {
     constexpr int U = kPrepUnroll;
     constexpr uint32_t kSub = kThreads * kPrepVec;
@@ -466,11 +485,11 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
     const AH_GLOBAL uint16_t *grad = nullptr;
     for (uint64_t w = blockIdx.x; w < total_tiles; w += gridDim.x) {
         if (w >= c_end) {
-            while (w >= tab[c + 1].tile_begin) ++c; /* sentinel row n_chunks ends the search */
-            grad = gptr<uint16_t>(tab[c].grad);
-            numel = tab[c].numel;
-            c_begin = tab[c].tile_begin;
-            c_end = tab[c + 1].tile_begin;
+            while (w >= tab.tile_begin(c + 1)) ++c; /* sentinel row n_chunks ends the search */
+            grad = gptr<uint16_t>(tab.grad(c));
+            numel = tab.numel(c);
+            c_begin = tab.tile_begin(c);
+            c_end = tab.tile_begin(c + 1);
         }
         const uint64_t e0 = (w - c_begin) * kTile;
         if (e0 + kTile <= numel) {
@@ -522,8 +541,29 @@ grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t t
         publish_total(res, s, inv_scale, extra_sumsq, accumulate);
         __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); /* re-arm */
     }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kThreads)
+grad_prep_kernel(const DevChunk *__restrict__ tab, uint32_t n_chunks, uint64_t total_tiles, double inv_scale,
+                 double extra_sumsq, uint32_t accumulate, double *partials, uint32_t *ticket, GradResult *res)
+{
+    grad_prep_body<DT>(TableInMemory{tab}, total_tiles, inv_scale, extra_sumsq, accumulate, partials, ticket, res);
     (void)n_chunks;
 }
+
+/* The same pass with the chunk list in the kernel arguments and the cross-block scratch (block
+ * partials, ticket) handed in by the launcher: nothing here was allocated for the call. */
+template <int DT>
+__global__ void __launch_bounds__(kThreads)
+grad_prep_args_kernel(const PrepRows rows, uint64_t total_tiles, double inv_scale, double extra_sumsq,
+                      double *partials, uint32_t *ticket, GradResult *res)
+{
+    grad_prep_body<DT>(TableInArgs{rows}, total_tiles, inv_scale, extra_sumsq, 0u, partials, ticket, res);
+}
+
+__global__ void clear_word_kernel(uint32_t *word) { *word = 0u; }
+
 
 /*
  * Second half of the norm carried by adamw_step_carry_kernel: sums the n wave partials in a
@@ -674,6 +714,74 @@ hipError_t launch_prep(int dtype, unsigned blocks, hipStream_t stream, const Dev
     else
         hipLaunchKernelGGL(grad_prep_kernel<kBF16>, dim3(blocks), dim3(kThreads), 0, stream, tab, n_chunks,
                            total_tiles, inv_scale, extra_sumsq, accumulate ? 1u : 0u, partials, ticket, res);
+    return hipGetLastError();
+}
+
+/* ------------------------------------------------------------------------------------- */
+/* The allocation-free norm pass                                                           */
+/* ------------------------------------------------------------------------------------- */
+
+/* Its cross-block scratch: kStaticMaxBlocks fp64 block partials followed by the ticket word.
+ * One copy per GPU, loaded with the code object and held until the process ends; every call on
+ * a GPU uses that GPU's copy, so calls that overlap on one GPU race.  In host code the name
+ * below is only a handle for hipGetSymbolAddress, never an address. */
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticSetup {
+    std::mutex lock;
+    void *ptr[kMaxDevices] = {};
+    int n_cu[kMaxDevices] = {};
+} g_static;
+}  // namespace
+
+/* Address of the current device's copy of `scratch` and that device's CU count, looked up once
+ * per device (with that device current) and kept. */
+static hipError_t static_scratch(void **ptr, int *n_cu)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(g_static.lock);
+    if (!g_static.ptr[dev]) {
+        void *p = nullptr;
+        int cu = 0;
+        if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+        if ((e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        if (!p || cu <= 0) return hipErrorInvalidSymbol;
+        g_static.n_cu[dev] = cu;
+        g_static.ptr[dev] = p;
+    }
+    *ptr = g_static.ptr[dev];
+    *n_cu = g_static.n_cu[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_prep_static(int dtype, hipStream_t stream, const PrepRows &rows, uint64_t total_tiles,
+                              double inv_scale, double extra_sumsq, GradResult *res)
+{
+    void *base = nullptr;
+    int n_cu = 0;
+    hipError_t e = static_scratch(&base, &n_cu);
+    if (e != hipSuccess) return e;
+    double *partials = static_cast<double *>(base);
+    uint32_t *ticket = reinterpret_cast<uint32_t *>(static_cast<unsigned char *>(base) +
+                                                    kStaticMaxBlocks * sizeof(double));
+    /* same grid rule as the workspace path: one block per CU, never more blocks than tiles */
+    uint64_t blocks = std::min<uint64_t>((uint64_t)std::min(n_cu, kStaticMaxBlocks), total_tiles);
+    if (blocks == 0) blocks = 1;
+    /* The array keeps whatever the last call left.  Only the ticket must start at zero (every
+     * partial that is read is written first); a kernel clears it, not a memset, so that the call
+     * can be recorded into a graph. */
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, stream, ticket);
+    if (dtype == kFP16)
+        hipLaunchKernelGGL(grad_prep_args_kernel<kFP16>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, rows,
+                           total_tiles, inv_scale, extra_sumsq, partials, ticket, res);
+    else
+        hipLaunchKernelGGL(grad_prep_args_kernel<kBF16>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, rows,
+                           total_tiles, inv_scale, extra_sumsq, partials, ticket, res);
     return hipGetLastError();
 }
 
