@@ -218,7 +218,9 @@ int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t
  * per iteration with the default tuning) and are summed into ws_next's result, by one small
  * kernel, on the stream of the next call that uses or reads that result -- which the caller has
  * to order after these updates anyway.  The buffer grows by doubling until it holds a whole
- * iteration; growing allocates and thereby waits for the device (first iteration only).
+ * iteration; growing allocates and thereby waits for the device (first iteration only), unless
+ * autohete_ws_tune(ws_next, AH_TUNE_CARRY_ELEMS, elements per iteration) has sized it beforehand:
+ * then no call of this function allocates or frees.
  * Errors: as autohete_adamw_step; AH_EINVAL also if ws_next is NULL or equals ws.
  */
 int autohete_adamw_step_carry(autohete_ws *ws, autohete_ws *ws_next, const autohete_chunk *chunks,
@@ -241,10 +243,17 @@ int autohete_grad_result_set(autohete_ws *ws, double sumsq, uint32_t found_inf, 
  * norm (last bits of S).
  */
 enum {
-    AH_TUNE_STEP_BLOCKS_PER_CU = 0, /* cap on step-kernel blocks resident per CU (1..64; 64 =
-                                       no cap); 0 = default                                    */
+    AH_TUNE_STEP_BLOCKS_PER_CU = 0, /* cap on step-kernel blocks resident per CU: 3..64 (64 = no
+                                       cap; 1 and 2 cannot be enforced and are refused with
+                                       AH_EINVAL); 0 = default                                 */
     AH_TUNE_PREP_BLOCKS = 1,        /* thread blocks of the prep kernel; 0 = default           */
     AH_TUNE_CAST_BLOCKS_PER_CU = 3, /* the same cap for the cast kernel; 0 = default           */
+    AH_TUNE_CARRY_ELEMS = 4,        /* elements that autohete_adamw_step_carry calls carry INTO
+                                       this workspace per iteration (the model's element count):
+                                       sizes the buffer of per-wavefront partials now (allocates,
+                                       waits for the device), so that no later call does.  Set
+                                       the step variant first; AH_EINVAL while a carried sum is
+                                       pending                                                 */
     AH_TUNE_STEP_VARIANT = 2        /* step-kernel variant: elements per lane (1, 2, 4)
                                        | mode << 4 (0 = fp64 Newton root/quotient, 1 = fp64
                                        correctly rounded) | (threads per block / 64) << 8;

@@ -14,6 +14,7 @@ AH_OK, AH_EINVAL, AH_EALIGN, AH_ENOMEM, AH_EHIP, AH_EINFEASIBLE, AH_ELIMIT = 0, 
 AUTOHETE_STATIC_MAX_CHUNKS = 128
 AH_BF16, AH_FP16 = 0, 1
 AH_TUNE_STEP_BLOCKS_PER_CU, AH_TUNE_PREP_BLOCKS, AH_TUNE_STEP_VARIANT, AH_TUNE_CAST_BLOCKS_PER_CU = 0, 1, 2, 3
+AH_TUNE_CARRY_ELEMS = 4
 
 
 def step_variant(vec=4, block=64, mode=0):

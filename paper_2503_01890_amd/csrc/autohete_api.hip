@@ -70,6 +70,7 @@ namespace {
  * Default: 4 elements per lane, one wavefront per block, Newton fp64, at most 10 blocks per CU. */
 constexpr int64_t kDefaultVariant = 4 | (0 << 4) | (1 << 8);
 constexpr int kDefaultBlocksPerCu = 10;
+constexpr int kDefaultMasterBlocksPerCu = 12; /* no 16-bit store: 10 -> 80.4, 11 -> 82.2, 12 -> 83.0, 14 -> 81.5 % of peak */
 constexpr int kDefaultCarryBlocksPerCu = 11; /* its waves live a little longer: 10 -> 28.9, 11 -> 28.5, 14 -> 29.0 ms */
 constexpr int kDefaultCastBlocksPerCu = 24; /* measured: 64 -> 6.38, 24 -> 6.88, 16 -> 6.10 TB/s */
 
@@ -202,8 +203,11 @@ int build_prep_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
  * each group can be launched as a 2-D grid (x = tile, y = row) in which at most half of the
  * blocks fall beyond the end of their chunk.  Equal-sized chunks form a single group. */
 int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, uint32_t tile_elems,
-                     unsigned need, hipStream_t stream, autohete_ws::Table **out)
+                     uint32_t block_threads, unsigned need, hipStream_t stream, autohete_ws::Table **out)
 {
+    /* A launch may have at most 2^31 - 1 blocks along x and fewer than 2^32 threads along x; a chunk
+     * with more tiles than that is refused here, before anything is launched for the call. */
+    const uint64_t max_tiles = std::min<uint64_t>(0x7FFFFFFFull, 0xFFFFFFFFull / block_threads);
     if (n > ws->max_chunks) return AH_ENOMEM;
     if (n && !chunks) return AH_EINVAL;
     std::vector<uint64_t> tiles(n);
@@ -213,7 +217,7 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
         int rc = validate_chunk(chunks[i], need);
         if (rc != AH_OK) return rc;
         tiles[i] = (chunks[i].numel + tile_elems - 1) / tile_elems;
-        if (tiles[i] > 0x7FFFFFFFull) return AH_EINVAL; /* grid.x limit: chunk too large */
+        if (tiles[i] > max_tiles) return AH_EINVAL; /* chunk too large for one launch of this kernel shape */
         bucket[i] = tiles[i] <= 1 ? 0 : 64 - (uint32_t)__builtin_clzll(tiles[i] - 1);
         ++count[bucket[i]];
     }
@@ -257,7 +261,11 @@ int build_step_table(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n, 
 }
 
 /* Cap on resident blocks per CU, enforced through the dynamic LDS request: the launcher asks for
- * 1/cap of a CU's LDS per block (the kernels themselves use none).  cap >= 64: no request. */
+ * 1/cap of a CU's LDS per block (the kernels themselves use none).  cap >= 64: no request.  A block
+ * may ask for at most 64 KB, so with 160 KB per CU the smallest cap this can express is 3
+ * (53 KB per block); autohete_ws_tune refuses 1 and 2. */
+constexpr int64_t kMinBlocksPerCu = 3;
+constexpr size_t kLdsPerCuGfx950 = 160 * 1024;
 unsigned lds_for_cap(const autohete_ws *ws, int64_t cap)
 {
     if (cap >= 64 || !ws->lds_per_cu) return 0;
@@ -374,7 +382,10 @@ int autohete_ws_create(autohete_ws **out, uint64_t max_chunks)
         return AH_EHIP;
     }
     ws->n_cu = prop.multiProcessorCount;
-    ws->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+    /* The residency caps divide the LDS of one CU.  This library is built for gfx950 only, whose CUs
+     * have 160 KB; a runtime that reports less (the 64 KB a single block may use) would silently turn
+     * a cap of 10 into 25. */
+    ws->lds_per_cu = std::max<size_t>(prop.maxSharedMemoryPerMultiProcessor, kLdsPerCuGfx950);
     bool ok = true;
     const size_t tab_bytes = (max_chunks + 1) * sizeof(DevChunk);
     /* As many cached tables and staging buffers as fit a few MB, at least the two a prep + step pair
@@ -442,13 +453,35 @@ int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value)
     if (!ws || value < 0) return AH_EINVAL;
     switch (knob) {
         case AH_TUNE_STEP_BLOCKS_PER_CU:
-            if (value > 64) return AH_EINVAL;
+            if (value > 64 || (value && value < kMinBlocksPerCu)) return AH_EINVAL;
             ws->tune_step_blocks_per_cu = value;
             return AH_OK;
         case AH_TUNE_CAST_BLOCKS_PER_CU:
-            if (value > 64) return AH_EINVAL;
+            if (value > 64 || (value && value < kMinBlocksPerCu)) return AH_EINVAL;
             ws->tune_cast_blocks_per_cu = value;
             return AH_OK;
+        case AH_TUNE_CARRY_ELEMS: {
+            /* Room for the per-wavefront partials that autohete_adamw_step_carry calls carry INTO this
+             * workspace during one iteration over `value` elements: one slot per 64 * vec elements
+             * (current step variant) plus, per chunk descriptor, the waves of one ragged last tile. */
+            ah::StepVariant v;
+            if (!decode_variant(ws->tune_step_variant, &v)) return AH_EINVAL;
+            DeviceGuard g(ws->device);
+            if (!g.ok) return AH_EHIP;
+            const uint64_t slots = (uint64_t)value / (uint64_t)(64 * v.vec) + (ws->max_chunks + 1) * 8;
+            if (slots <= ws->wave_partials_cap) return AH_OK;
+            if (ws->carried_slots) return AH_EINVAL; /* a carried sum is pending: fold it first (read the result) */
+            if (hipDeviceSynchronize() != hipSuccess) return AH_EHIP;
+            if (ws->d_wave_partials) (void)hipFree(ws->d_wave_partials);
+            ws->d_wave_partials = nullptr;
+            ws->wave_partials_cap = 0;
+            if (hipMalloc(&ws->d_wave_partials, slots * sizeof(double)) != hipSuccess) {
+                (void)hipGetLastError();
+                return AH_ENOMEM;
+            }
+            ws->wave_partials_cap = slots;
+            return AH_OK;
+        }
         case AH_TUNE_PREP_BLOCKS:
             if (value > ah::kMaxPartials) return AH_EINVAL;
             ws->tune_prep_blocks = value;
@@ -579,7 +612,7 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     autohete_ws::Table *tab = nullptr;
     int rc;
     try {
-        rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block),
+        rc = build_step_table(ws, chunks, n_chunks, (uint32_t)(var.vec * var.block), (uint32_t)var.block,
                               kGrad | kMaster | kMom1 | kMom2 | (write_back ? kLowp : 0u), stream, &tab);
     } catch (...) {
         return AH_ENOMEM;
@@ -605,7 +638,8 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     k.wd = (double)hp->weight_decay;
 
     const unsigned lds = lds_for_cap(ws, ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu
-                                         : carry_to ? kDefaultCarryBlocksPerCu : kDefaultBlocksPerCu);
+                                         : carry_to ? kDefaultCarryBlocksPerCu
+                                         : write_back ? kDefaultBlocksPerCu : kDefaultMasterBlocksPerCu);
     if (!carry_to) {
         for (const autohete_ws::Group &grp : tab->groups) {
             if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
@@ -657,7 +691,7 @@ int autohete_cast_params(autohete_ws *ws, const autohete_chunk *chunks, uint64_t
     autohete_ws::Table *tab = nullptr;
     int rc;
     try {
-        rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, kLowp | kMaster, stream, &tab);
+        rc = build_step_table(ws, chunks, n_chunks, ah::kCastTileElems, 64u, kLowp | kMaster, stream, &tab);
     } catch (...) {
         return AH_ENOMEM;
     }

@@ -184,8 +184,10 @@ bool have_avx512()
 
 /* ---------------------------------------------------------------- threading */
 
-/* Cuts the concatenated element space of the chunks into n_threads contiguous slices (multiples of
- * 16 elements inside a chunk) and runs fn(chunk index, lo, hi, thread) for every piece. */
+/* Cuts the concatenated element space of the chunks into n_threads contiguous slices of a multiple
+ * of 16 elements each and runs fn(chunk index, lo, hi, thread) for every piece.  A piece starts
+ * wherever its slice meets the chunk: with ragged chunk sizes that is any element, so fn must not
+ * assume alignment (the vector paths use unaligned loads and stores). */
 template <typename F>
 void for_slices(const autohete_chunk *chunks, uint64_t n, int n_threads, F fn)
 {

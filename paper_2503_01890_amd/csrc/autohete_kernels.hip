@@ -236,15 +236,9 @@ __device__ __forceinline__ typename VecTypes<VEC>::f32 join(const float *in)
  * footnote on GPU-resident optimizer states).
  */
 template <int DT, int VEC, int BS, int MODE, bool WB>
-__global__ void __launch_bounds__(BS)
-adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k)
+__device__ __forceinline__ void step_tile(const GradResult &r, const DevChunk &ch, const StepConsts &k, uint32_t tile)
 {
-    /* Both scalar fetches (the 32-byte result, the 64-byte table row) are issued together and
-     * feed ONE exit test, so a wave pays two dependent scalar round trips (kernel arguments,
-     * then these) before its vector loads instead of six. */
-    const GradResult r = *res;
-    const DevChunk ch = tab[blockIdx.y];
-    const uint64_t off = (uint64_t)blockIdx.x * (BS * VEC) + threadIdx.x * VEC;
+    const uint64_t off = (uint64_t)tile * (BS * VEC) + threadIdx.x * VEC;
     /* Skip-on-overflow: leave before the first load, no stream is touched.  Also leave if this
      * tile lies beyond the chunk (grid.x is the largest tile count of the launch group). */
     if (r.found_inf | (uint32_t)(off >= ch.numel)) return;
@@ -280,6 +274,18 @@ adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict
             if constexpr (WB) gptr<uint16_t>(ch.param_lp)[i] = (uint16_t)f32_to_lowp<DT>(p);
         }
     }
+}
+
+template <int DT, int VEC, int BS, int MODE, bool WB>
+__global__ void __launch_bounds__(BS)
+adamw_step_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k)
+{
+    /* Both scalar fetches (the 32-byte result, the 64-byte table row) are issued together and
+     * feed ONE exit test, so a wave pays two dependent scalar round trips (kernel arguments,
+     * then these) before its vector loads instead of six. */
+    const GradResult r = *res;
+    const DevChunk ch = tab[blockIdx.y];
+    step_tile<DT, VEC, BS, MODE, WB>(r, ch, k, blockIdx.x);
 }
 
 /* Sum of x over the 64 lanes of a wavefront, returned in every lane, in a fixed order and
@@ -322,13 +328,10 @@ __device__ __forceinline__ double wave_sum(double x)
  * skip (res->found_inf) the streams are left alone but the squares are still gathered.
  */
 template <int DT, int VEC, int BS, int MODE>
-__global__ void __launch_bounds__(BS)
-adamw_step_carry_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k,
-                        double *__restrict__ wave_partials, uint64_t slot_base)
+__device__ __forceinline__ void carry_tile(const GradResult &r, const DevChunk &ch, const StepConsts &k, uint32_t tile,
+                                           double *__restrict__ wave_partials, uint64_t slot_base)
 {
-    const GradResult r = *res;
-    const DevChunk ch = tab[blockIdx.y];
-    const uint64_t tile0 = (uint64_t)blockIdx.x * (BS * VEC);
+    const uint64_t tile0 = (uint64_t)tile * (BS * VEC);
     /* A whole block beyond the chunk owns no slot and leaves.  The flag (0 or 1) takes part in the
      * test only so that the result is fetched together with the table row, ahead of the branch,
      * as in adamw_step_kernel: one dependent scalar round trip fewer before the vector loads. */
@@ -379,7 +382,17 @@ adamw_step_carry_kernel(const DevChunk *__restrict__ tab, const GradResult *__re
     /* all 64 lanes of every wave of the block arrive here (lanes beyond the chunk carry 0) */
     sq = wave_sum(sq);
     if ((threadIdx.x & 63) == 0)
-        wave_partials[slot_base + (ch.tile_begin + blockIdx.x) * (BS / 64) + (threadIdx.x >> 6)] = sq;
+        wave_partials[slot_base + (ch.tile_begin + tile) * (BS / 64) + (threadIdx.x >> 6)] = sq;
+}
+
+template <int DT, int VEC, int BS, int MODE>
+__global__ void __launch_bounds__(BS)
+adamw_step_carry_kernel(const DevChunk *__restrict__ tab, const GradResult *__restrict__ res, StepConsts k,
+                        double *__restrict__ wave_partials, uint64_t slot_base)
+{
+    const GradResult r = *res;
+    const DevChunk ch = tab[blockIdx.y];
+    carry_tile<DT, VEC, BS, MODE>(r, ch, k, blockIdx.x, wave_partials, slot_base);
 }
 
 /*
@@ -477,22 +490,28 @@ grad_prep_body(const Table tab, uint64_t total_tiles, double inv_scale, double e
      * the end.  fp64 cannot overflow on finite 16-bit inputs, so a non-finite total means a
      * non-finite gradient: the finite check costs no extra instruction per element. */
     double acc0 = 0.0, acc1 = 0.0;
-    /* Chunk cursor: the row of the current chunk is re-read only when the tile index leaves the
-     * chunk (wave-uniform, scalar), so the steady-state iteration issues its vector loads
-     * without waiting on a scalar fetch. */
+    /* Chunk cursor: the row of a tile's chunk is looked up (wave-uniform, scalar) only when the
+     * tile index leaves the current chunk, and always one tile AHEAD: the lookup for the next tile
+     * is issued right behind the current tile's vector loads and completes under them, so no
+     * iteration waits for a scalar fetch before it can issue its loads.  (With chunks of 256 tiles
+     * and 256 blocks every iteration changes chunk: looked up in line, that cost about a third of
+     * the pass on the 124M-parameter model.) */
+    struct Row {
+        const AH_GLOBAL uint16_t *grad;
+        uint64_t numel, begin, end;
+    };
     uint32_t c = 0;
-    uint64_t c_begin = 0, c_end = 0, numel = 0;
-    const AH_GLOBAL uint16_t *grad = nullptr;
+    auto lookup = [&](uint64_t w) {
+        while (w >= tab.tile_begin(c + 1)) ++c; /* sentinel row n_chunks ends the search */
+        return Row{gptr<uint16_t>(tab.grad(c)), tab.numel(c), tab.tile_begin(c), tab.tile_begin(c + 1)};
+    };
+    Row cur{nullptr, 0, 0, 0};
+    if (blockIdx.x < total_tiles) cur = lookup(blockIdx.x);
     for (uint64_t w = blockIdx.x; w < total_tiles; w += gridDim.x) {
-        if (w >= c_end) {
-            while (w >= tab.tile_begin(c + 1)) ++c; /* sentinel row n_chunks ends the search */
-            grad = gptr<uint16_t>(tab.grad(c));
-            numel = tab.numel(c);
-            c_begin = tab.tile_begin(c);
-            c_end = tab.tile_begin(c + 1);
-        }
-        const uint64_t e0 = (w - c_begin) * kTile;
-        if (e0 + kTile <= numel) {
+        const uint64_t e0 = (w - cur.begin) * kTile;
+        const uint64_t w_next = w + gridDim.x;
+        Row next = cur;
+        if (e0 + kTile <= cur.numel) {
             /* All U loads are issued, in order, before the first square; the squares then follow in
              * the same order, each group waiting only for its own load (vmcnt U-1, U-2, ...), so the
              * arithmetic runs under the arrival of the later loads.  The barriers pin that order:
@@ -500,9 +519,11 @@ grad_prep_body(const Table tab, uint64_t total_tiles, double inv_scale, double e
             u32x4 g[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                g[u] = ld<true>((const AH_GLOBAL u32x4 *)(grad + e0 + (uint64_t)u * kSub + threadIdx.x * kPrepVec));
+                g[u] = ld<true>((const AH_GLOBAL u32x4 *)(cur.grad + e0 + (uint64_t)u * kSub + threadIdx.x * kPrepVec));
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (w_next < total_tiles && w_next >= cur.end) next = lookup(w_next);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -515,12 +536,14 @@ grad_prep_body(const Table tab, uint64_t total_tiles, double inv_scale, double e
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
-            const uint64_t end = e0 + kTile < numel ? e0 + kTile : numel;
+            const uint64_t end = e0 + kTile < cur.numel ? e0 + kTile : cur.numel;
             for (uint64_t i = e0 + threadIdx.x; i < end; i += kThreads) {
-                const double x = (double)lowp_to_f32<DT>(grad[i]);
+                const double x = (double)lowp_to_f32<DT>(cur.grad[i]);
                 acc0 += x * x;
             }
+            if (w_next < total_tiles && w_next >= cur.end) next = lookup(w_next);
         }
+        cur = next;
     }
     const double bsum = block_sum(acc0 + acc1, lds4);
 
@@ -563,7 +586,6 @@ grad_prep_args_kernel(const PrepRows rows, uint64_t total_tiles, double inv_scal
 }
 
 __global__ void clear_word_kernel(uint32_t *word) { *word = 0u; }
-
 
 /*
  * Second half of the norm carried by adamw_step_carry_kernel: sums the n wave partials in a
