@@ -8,7 +8,7 @@ import torch
 
 import oracle
 from _golden import load_hand_worked
-from _harness import (compare_state, download, oracle_hp, random_state, stream_handle, upload)
+from _harness import (FreeRun, StepCtx, compare_state, download, oracle_hp, random_state, stream_handle, upload)
 from paper_2503_01890_amd import binding as B
 from paper_2503_01890_amd.modeldata import ModelData, STREAMS
 
@@ -27,12 +27,27 @@ def run_gpu(md, ws, dtype, step, hp, extra=0.0, indices=None):
     return norm, flag
 
 
-def run_oracle(states, dtype, step, hp, extra=0.0):
-    """Steps the oracle in place; the pre-step master and first moment are kept under "old"."""
+def run_oracle(states, dtype, step, hp, extra=0.0, ws=None):
+    """Steps the oracle in place; the pre-step state is kept under "old" and what the comparison
+    rules need to know about the step under "ctx" (with the GPU's sum of squares when the
+    workspace that holds it is given)."""
     for st in states:
         st["old"] = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(),
                          exp_avg_sq=st["exp_avg_sq"].copy())
-    return oracle.full_step(states, dtype, step, oracle_hp(hp), extra)
+    norm, flag = oracle.full_step(states, dtype, step, oracle_hp(hp), extra)
+    sumsq_gpu = ws.autohete_grad_result_get(stream_handle())[0] if (ws is not None and not flag) else None
+    for st in states:
+        st["ctx"] = StepCtx(dtype, hp, step, norm, sumsq_gpu)
+    return norm, flag
+
+
+F32_AND_LP = ("param_lp", "master", "exp_avg", "exp_avg_sq")
+
+
+def resync(md, states, indices=None):
+    """Oracle -> device: the next step starts from identical inputs on both sides."""
+    for i, st in enumerate(states):
+        upload(md, i if indices is None else indices[i], {k: st[k] for k in F32_AND_LP})
 
 
 def check_norm(gn, gf, on, of):
@@ -53,10 +68,42 @@ def test_single_chunk_odd_sizes(dtype, n):
     hp = B.hparams(loss_scale=scale)
     for step in (1, 2, 3):
         gn, gf = run_gpu(md, ws, dtype, step, hp)
-        on, of = run_oracle([st], dtype, step, hp)
+        on, of = run_oracle([st], dtype, step, hp, ws=ws)
         check_norm(gn, gf, on, of)
-        compare_state(download(md, 0), st, "n=%d step=%d" % (n, step), st["old"], drift_steps=step - 1)
+        compare_state(download(md, 0), st, "n=%d step=%d" % (n, step), st["old"])
+        resync(md, [st])
     assert np.array_equal(download(md, 0)["grad"], st["grad"])          # gradients are read only
+    ws.close()
+
+
+@pytest.mark.parametrize("dtype", [B.AH_BF16, B.AH_FP16])
+def test_forty_free_running_steps_stay_inside_the_carried_bound(dtype):
+    """The device state is never re-synchronised with the oracle's: forty consecutive steps with
+    fresh gradients and active clipping, every element held to the bound that is carried along
+    with the oracle's state (tests/parity_check.c, parity_free)."""
+    rng = np.random.default_rng(321 + dtype)
+    n = 3 * 65536 + 77
+    scale = 1.0 if dtype == B.AH_BF16 else 512.0
+    st = random_state(n, dtype, rng, scale=scale)
+    md = ModelData([n])
+    upload(md, 0, st)
+    ws = B.Workspace(1)
+    hp = B.hparams(loss_scale=scale, max_grad_norm=0.3)
+    bound = FreeRun(n)
+    worst = {}
+    for step in range(1, 41):
+        st["grad"] = random_state(n, dtype, rng, scale=scale)["grad"]
+        upload(md, 0, dict(grad=st["grad"]))
+        gn, gf = run_gpu(md, ws, dtype, step, hp)
+        on, of = run_oracle([st], dtype, step, hp, ws=ws)
+        check_norm(gn, gf, on, of)
+        stats = bound.step(download(md, 0), st, st["old"], st["ctx"], "free-running step %d" % step)
+        for k, v in stats.items():
+            worst[k] = max(worst.get(k, 0), v)
+    for s in ("master", "exp_avg", "exp_avg_sq"):
+        assert worst[s + "_fail"] == 0 and worst[s + "_max_E_frac"] <= 1.0
+    print("free-running, 40 steps: worst error / bound E: m %.3f v %.3f p %.3f; worst error in ulp32(T): m %.2f v %.2f p %.2f"
+          % tuple(worst[s + f] for f in ("_max_E_frac", "_max_ulp_T") for s in ("exp_avg", "exp_avg_sq", "master")))
     ws.close()
 
 
@@ -75,11 +122,11 @@ def test_every_kernel_variant_ragged_multichunk(variant, dtype):
     hp = B.hparams(max_grad_norm=0.05)
     for step in (1, 2):
         gn, gf = run_gpu(md, ws, dtype, step, hp, extra=1e-4)
-        on, of = run_oracle(states, dtype, step, hp, extra=1e-4)
+        on, of = run_oracle(states, dtype, step, hp, extra=1e-4, ws=ws)
         check_norm(gn, gf, on, of)
         for i, st in enumerate(states):
-            compare_state(download(md, i), st, "variant=%x chunk=%d" % (variant, i), st["old"],
-                              drift_steps=step - 1)
+            compare_state(download(md, i), st, "variant=%x chunk=%d" % (variant, i), st["old"])
+        resync(md, states)
     ws.close()
 
 
@@ -276,10 +323,72 @@ def test_error_codes():
     assert lib.autohete_ws_tune(h, 99, 1) == B.AH_EINVAL
     assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_VARIANT, 3) == B.AH_EINVAL
     assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_BLOCKS_PER_CU, 65) == B.AH_EINVAL
+    for knob in (B.AH_TUNE_STEP_BLOCKS_PER_CU, B.AH_TUNE_CAST_BLOCKS_PER_CU):
+        for cap in (1, 2):            # the residency cap works through the LDS request: 1 and 2 cannot be enforced
+            assert lib.autohete_ws_tune(h, knob, cap) == B.AH_EINVAL
+        for cap in (3, 64, 0):
+            assert lib.autohete_ws_tune(h, knob, cap) == B.AH_OK
+    # A chunk with more tiles than one launch of the selected kernel shape can have is refused before
+    # anything is launched (the pointers are never touched: no kernel runs for the call).
+    huge = list(t)
+    huge[5] = (1 << 33) + 16
+    assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_VARIANT, B.step_variant(1, 128, 0)) == B.AH_OK
+    assert step(B.chunk_array([huge]), 1) == B.AH_EINVAL              # 2^26 blocks of 128 threads: 2^33 threads along x
+    assert step(B.chunk_array([t, huge]), 2) == B.AH_EINVAL           # ... also behind a chunk that would be fine
+    assert lib.autohete_ws_tune(h, B.AH_TUNE_STEP_VARIANT, 0) == B.AH_OK
+    huge[5] = 1 << 40
+    assert step(B.chunk_array([huge]), 1) == B.AH_EINVAL              # 2^32 tiles of the default shape
+    assert lib.autohete_cast_params(h, B.chunk_array([huge]), 1, B.AH_BF16, s) == B.AH_EINVAL
     torch.cuda.synchronize()
     got = download(md, 0)
     assert not got["exp_avg"].any()                                   # rejected calls launched nothing harmful
     ws.close()
+
+
+def test_presized_carry_buffer_means_no_allocation_in_any_iteration():
+    """autohete_adamw_step_carry appends one fp64 slot per wavefront to a buffer of the receiving
+    workspace.  Sized beforehand (AH_TUNE_CARRY_ELEMS), no call allocates or frees: the device's
+    free memory is the same after every iteration, the first included, and the results are those
+    of a workspace that grew its buffer on demand."""
+    rng = np.random.default_rng(4242)
+    C, n_chunks = 1 << 20, 6
+    states = [random_state(C, B.AH_BF16, rng) for _ in range(n_chunks)]
+    a, b = ModelData([C] * n_chunks), ModelData([C] * n_chunks)
+    for i, st in enumerate(states):
+        upload(a, i, st)
+        upload(b, i, st)
+    hp = B.hparams(max_grad_norm=0.0)        # no clipping: the streams do not depend on the last bits of the sums
+    s = stream_handle()
+    pre = [B.Workspace(n_chunks + 2), B.Workspace(n_chunks + 2)]
+    grow = [B.Workspace(n_chunks + 2), B.Workspace(n_chunks + 2)]
+    for w in pre:
+        w.tune(B.AH_TUNE_CARRY_ELEMS, C * n_chunks)
+    parts = [(i * C // 2, (i + 1) * C // 2) for i in range(2 * n_chunks)]        # "blocks" of half a chunk
+    torch.cuda.synchronize()
+    free = [torch.cuda.mem_get_info()[0]]
+    sums = {}
+    for name, md, wss in (("pre", a, pre), ("grow", b, grow)):
+        wss[1].autohete_grad_result_set(0.0, 0, s)
+        for it in (1, 2, 3):
+            cur, nxt = wss[it % 2], wss[(it + 1) % 2]
+            nxt.autohete_grad_result_set(0.0, 0, s)
+            for lo, hi in reversed(parts):
+                tup = md.range_tuples(lo, hi)
+                cur.autohete_adamw_step_carry(nxt, B.chunk_array(tup), len(tup), B.AH_BF16, it, hp, s)
+            sums[name, it] = nxt.autohete_grad_result_get(s)[0]
+            if name == "pre":
+                free.append(torch.cuda.mem_get_info()[0])
+    assert len(set(free)) == 1, free
+    # a buffer that fills up is folded early: the same sum in another order of fp64 additions
+    assert all(abs(sums["pre", it] - sums["grow", it]) <= 1e-13 * sums["grow", it] for it in (1, 2, 3))
+    for i in range(n_chunks):
+        x, y = download(a, i), download(b, i)
+        assert all(x[k].tobytes() == y[k].tobytes() for k in STREAMS)
+    with pytest.raises(B.AutoheteError):                 # not while a carried sum is pending
+        pre[0].autohete_adamw_step_carry(pre[1], a.chunk_array(), n_chunks, B.AH_BF16, 4, hp, s)
+        pre[1].tune(B.AH_TUNE_CARRY_ELEMS, 64 * C * n_chunks)
+    for w in pre + grow:
+        w.close()
 
 
 def test_padding_stays_zero_and_checkpoint_resume():
@@ -347,20 +456,28 @@ def test_split_path_master_only_step_then_cast(dtype):
             assert np.array_equal(download(split, i, ("param_lp",))["param_lp"], before[i])
         ws.autohete_cast_params(arr, n, dtype, stream_handle())
         torch.cuda.synchronize()
-        run_oracle(states, dtype, step, hp)
+        run_oracle(states, dtype, step, hp, ws=ws)
         for i, st in enumerate(states):
             a, b = download(fused, i), download(split, i)
             assert all(a[s].tobytes() == b[s].tobytes() for s in STREAMS), (step, i)
-            compare_state(b, st, "split step=%d chunk=%d" % (step, i), st["old"], drift_steps=step - 1)
-    # cast alone: any fp32 values, incl. ties, overflow to inf (fp16), subnormals, zeros, NaN stays NaN
-    vals = np.concatenate([rng.normal(0, 1, 5000), [0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e-8, 6e-8, -3e-8, 3.4e38],
+            compare_state(b, st, "split step=%d chunk=%d" % (step, i), st["old"])
+        resync(fused, states)
+        resync(split, states)
+    # cast alone: any fp32 values, incl. ties, overflow to inf (fp16), subnormals, zeros, +-inf; NaN stays NaN
+    vals = np.concatenate([rng.normal(0, 1, 5000), [0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e-8, 6e-8, -3e-8, 3.4e38,
+                                                    np.inf, -np.inf, np.nan, -np.nan, -65520.0, -3.4e38, 1e-45],
                            np.float32(1.0) + np.arange(0, 64) * np.float32(2.0 ** -12)]).astype(np.float32)
     md = ModelData([vals.size])
     md.view("master", 0).copy_(torch.from_numpy(vals))
     ws.autohete_cast_params(md.chunk_array(), 1, dtype, stream_handle())
     torch.cuda.synchronize()
     got = download(md, 0, ("param_lp",))["param_lp"]
-    assert np.array_equal(got, oracle.encode(vals, dtype))
+    want = oracle.encode(vals, dtype)
+    is_nan = np.isnan(vals)
+    assert is_nan.sum() == 2 and np.array_equal(got[~is_nan], want[~is_nan])
+    # a NaN stays a NaN (its sign and payload bits are not part of the rule)
+    assert np.all(np.isnan(oracle.decode(got[is_nan], dtype))) and np.all(np.isnan(oracle.decode(want[is_nan], dtype)))
+    assert np.array_equal(oracle.decode(got[np.isinf(vals)], dtype), vals[np.isinf(vals)])
     lib, s = B.raw(), ctypes.c_void_p(stream_handle())
     t = list(md.chunk_tuple(0))
     t[2] = None
@@ -468,7 +585,12 @@ def test_hybrid_placement_step_matches_oracle():
                 c = i - n_res
                 got = dict(master=host.master[c], exp_avg=host.exp_avg[c], exp_avg_sq=host.exp_avg_sq[c],
                            param_lp=host.dev_view("param_lp", c).cpu().numpy().view(np.uint16))
-            compare_state(got, st, "hybrid step=%d chunk=%d" % (step, i), st["old"], drift_steps=step - 1)
+            compare_state(got, st, "hybrid step=%d chunk=%d" % (step, i), st["old"])
+            if i < n_res:                       # oracle -> both halves: the next step starts identical
+                upload(md, i, {k: st[k] for k in F32_AND_LP})
+            else:
+                host.master[c][:], host.exp_avg[c][:], host.exp_avg_sq[c][:] = st["master"], st["exp_avg"], st["exp_avg_sq"]
+                host.dev_view("param_lp", c).copy_(torch.from_numpy(st["param_lp"].view(np.int16)))
     # overflow in a HOST-owned gradient: the GPU's norm sees it, both halves skip
     bad = states[n_res + 1]["grad"].copy()
     bad[99] = 0x7F80
@@ -538,7 +660,7 @@ def test_single_chunk_beyond_2_to_32_elements():
         for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):
             a = md.view(s, 0)[lo:lo + k].cpu().numpy()
             got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
-        compare_state(got, ref, "huge chunk window at %d" % lo, old)
+        compare_state(got, ref, "huge chunk window at %d" % lo, old, StepCtx(oracle.BF16, hp, 1, on))
     ws.close()
 
 
@@ -576,9 +698,10 @@ def test_random_hyperparameters_and_steps(seed):
             st["old"] = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(), exp_avg_sq=st["exp_avg_sq"].copy())
         on, of = oracle.full_step(states, dtype, step, ohp, extra)
         check_norm(gn, gf, on, of)
+        ctx = StepCtx(dtype, hp, step, on, ws.autohete_grad_result_get(stream_handle())[0])
         for i, st in enumerate(states):
-            compare_state(download(md, i), st, "seed=%d %r step=%d chunk=%d" % (seed, kw, step, i), st["old"],
-                          drift_steps=1)
+            compare_state(download(md, i), st, "seed=%d %r step=%d chunk=%d" % (seed, kw, step, i), st["old"], ctx)
+        resync(md, states)
     ws.close()
 
 
@@ -608,7 +731,10 @@ def test_seventy_thousand_tiny_chunks_cross_the_grid_row_limit():
     for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):
         a = md.slab[s][dev_idx].cpu().numpy()
         got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
-    compare_state(got, flat, "70k chunks", old)
+    compare_state(got, flat, "70k chunks", old, StepCtx(oracle.BF16, hp, 3, on))
+    for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):      # oracle -> device before the next step
+        a = flat[s]
+        md.slab[s][dev_idx] = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev_idx.device)
     # the norm-carrying update over the same 70k rows: its per-wave slots must stay consecutive across launch groups
     other = B.Workspace(n_chunks)
     other.autohete_grad_result_set(0.0, 0, stream_handle())
@@ -623,7 +749,7 @@ def test_seventy_thousand_tiny_chunks_cross_the_grid_row_limit():
     for s in ("param_lp", "master", "exp_avg", "exp_avg_sq"):
         a = md.slab[s][dev_idx].cpu().numpy()
         got[s] = a.view(np.uint16).copy() if a.dtype == np.int16 else a.copy()
-    compare_state(got, flat, "70k chunks, carry", old, drift_steps=1)
+    compare_state(got, flat, "70k chunks, carry", old, StepCtx(oracle.BF16, hp, 4, on))
     other.close()
     ws.close()
 
@@ -645,12 +771,13 @@ def test_two_workspaces_on_two_streams_do_not_interfere():
                 arr = md.chunk_array()
                 ws.autohete_grad_prep(arr, 2, B.AH_BF16, 1.0, 0.0, stream.cuda_stream)
                 ws.autohete_adamw_step(arr, 2, B.AH_BF16, rep + 1, hp, stream.cuda_stream)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        for states, md, ws, stream, hp in sets:
+            run_oracle(states, oracle.BF16, rep + 1, hp, ws=ws)
+            for i, st in enumerate(states):
+                compare_state(download(md, i), st, "two streams", st["old"])
+            resync(md, states)
     for states, md, ws, stream, hp in sets:
-        for rep in range(3):
-            run_oracle(states, oracle.BF16, rep + 1, hp)
-        for i, st in enumerate(states):
-            compare_state(download(md, i), st, "two streams", st["old"], drift_steps=3)
         ws.close()
 
 
@@ -702,7 +829,7 @@ def test_norm_carrying_step_equals_accumulate_then_step(variant, dtype):
         old = dict(master=st["master"].copy(), exp_avg=st["exp_avg"].copy(), exp_avg_sq=st["exp_avg_sq"].copy())
         oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"], dtype, 3,
                            oracle_hp(hp), 0.3, 0)
-        compare_state(a, st, "carry variant=%x chunk=%d" % (variant, i), old)
+        compare_state(a, st, "carry variant=%x chunk=%d" % (variant, i), old, StepCtx(dtype, hp, 3, 0.3))
     # the same launch again: the carried sum is bit-reproducible
     nxt.autohete_grad_result_set(carried_in, 0, s)
     cur.autohete_grad_result_set(0.0, 1, s)              # flagged: no stream may change, squares still gathered
@@ -769,7 +896,8 @@ def test_norm_carrying_step_lagged_pipeline_against_oracle():
                            exp_avg_sq=st["exp_avg_sq"].copy())
                 oracle.adamw_chunk(st["grad"], st["param_lp"], st["master"], st["exp_avg"], st["exp_avg_sq"],
                                    oracle.BF16, it, oracle_hp(hp), float(np.sqrt(prev_sumsq)), 0)
-                compare_state(download(md, i), st, "lagged it=%d chunk=%d" % (it, i), old)
+                compare_state(download(md, i), st, "lagged it=%d chunk=%d" % (it, i), old,
+                              StepCtx(oracle.BF16, hp, it, float(np.sqrt(prev_sumsq))))
                 upload(md, i, st)                        # oracle -> device, so each step starts from equal inputs
         prev_sumsq = o_sumsq
     for w in ws:
@@ -914,7 +1042,8 @@ def test_more_chunk_lists_than_cached_tables_and_a_second_stream():
         torch.cuda.synchronize()
         for i, st in enumerate(states):
             run_oracle([st], B.AH_BF16, step, hp)
-            compare_state(download(md, i), st, "cycle %d chunk %d" % (step, i), st["old"], drift_steps=step - 1)
+            compare_state(download(md, i), st, "cycle %d chunk %d" % (step, i), st["old"])
+            resync(md, [st], [i])
     side = torch.cuda.Stream()                           # default priority
     torch.cuda.synchronize()
     fresh = md.chunk_array([3, 5, 8])                    # a list this workspace has not seen
@@ -1055,3 +1184,56 @@ def test_exact_mode_is_bit_identical_to_the_oracle_given_the_same_norm(dtype):
         upload(fast, 0, st)                                  # both continue from the oracle's state
     ws_e.close()
     ws_f.close()
+
+
+def test_prep_and_step_captured_in_a_hip_graph_replay_like_eager_calls():
+    """One optimizer step (autohete_grad_prep + autohete_adamw_step) recorded into a HIP graph.
+    After a warm-up call on the capture stream the library finds its chunk tables on the device, so
+    the recording holds the two kernels and nothing else (no upload, no memset node).  The graph is
+    replayed four times with eager work and synchronisations of the same process in between; after
+    every replay the state must equal, bit for bit, that of a second copy stepped eagerly."""
+    rng = np.random.default_rng(515)
+    numels = [200_000, 65536, 33_333]
+    states = [random_state(n, B.AH_BF16, rng) for n in numels]
+    graph_md, eager_md = ModelData(numels), ModelData(numels)
+    for i, st in enumerate(states):
+        upload(graph_md, i, st)
+        upload(eager_md, i, st)
+    hp = B.hparams(max_grad_norm=0.05)
+    ws_g, ws_e = B.Workspace(3), B.Workspace(3)
+    side = torch.cuda.Stream()                                     # default priority
+    arr_g, arr_e = graph_md.chunk_array(), eager_md.chunk_array()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):                                  # warm-up: the tables are uploaded here
+        ws_g.autohete_grad_prep(arr_g, 3, B.AH_BF16, 1.0, 0.0, side.cuda_stream)
+        ws_g.autohete_adamw_step(arr_g, 3, B.AH_BF16, 1, hp, side.cuda_stream)
+    side.synchronize()
+    ws_e.autohete_grad_prep(arr_e, 3, B.AH_BF16, 1.0, 0.0, stream_handle())
+    ws_e.autohete_adamw_step(arr_e, 3, B.AH_BF16, 1, hp, stream_handle())
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        ws_g.autohete_grad_prep(arr_g, 3, B.AH_BF16, 1.0, 0.0, side.cuda_stream)
+        ws_g.autohete_adamw_step(arr_g, 3, B.AH_BF16, 2, hp, side.cuda_stream)   # the step number is part of the recording
+    torch.cuda.synchronize()
+    for i in range(3):                                             # recording runs nothing
+        a, b = download(graph_md, i), download(eager_md, i)
+        assert all(a[k].tobytes() == b[k].tobytes() for k in STREAMS)
+    scratch = torch.zeros(1 << 20, device="cuda:0")
+    for rep in range(4):
+        fresh = [random_state(n, B.AH_BF16, rng)["grad"] for n in numels]
+        for i, gr in enumerate(fresh):                             # eager work between the replays
+            upload(graph_md, i, dict(grad=gr))
+            upload(eager_md, i, dict(grad=gr))
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        ws_e.autohete_grad_prep(arr_e, 3, B.AH_BF16, 1.0, 0.0, stream_handle())
+        ws_e.autohete_adamw_step(arr_e, 3, B.AH_BF16, 2, hp, stream_handle())
+        torch.cuda.synchronize()
+        assert ws_g.autohete_grad_result_get(stream_handle()) == ws_e.autohete_grad_result_get(stream_handle())
+        for i in range(3):
+            a, b = download(graph_md, i), download(eager_md, i)
+            assert all(a[k].tobytes() == b[k].tobytes() for k in STREAMS), (rep, i)
+    assert float(scratch[0]) == 4.0
+    ws_g.close(), ws_e.close()

@@ -5,10 +5,17 @@ of the seeded generator; the oracle regenerates what it needs on the CPU from th
     (plus, for the half-resident workload, the host-side partial sum);
   - full element-by-element state of every chunk (124M and 1.3B configurations) or of a sample
     of 16 to 32 chunks (first, last/padded, tensor-boundary holders, seeded random ones),
-    replayed through every iteration.  After each iteration's
-    comparison the ORACLE's state of those chunks is uploaded over the device's, so that every
-    step is judged from identical inputs (data flows oracle -> device only, never back);
-    one sampled chunk is left free-running and judged with the drift allowance instead.
+    replayed through every iteration.
+Each sampled chunk is held on the device three times:
+  main   stepped with the whole model.  After each iteration's comparison the ORACLE's state is
+         uploaded over it (data flows oracle -> device only, never back), so every step is judged
+         from identical inputs by the strict rule (2 fp32 ulp / relative 1e-6; tests/parity_check.c);
+  free   a second copy stepped by the same default kernel with the same norm and never
+         re-synchronised: it runs free for all iterations and every element is held to the
+         rigorous per-element bound that is carried along with the oracle's state;
+  exact  a third copy stepped by the kernel's exact mode with the ORACLE's sum of squares handed
+         in: it must stay bit-identical to the oracle in every element of all four streams
+         through all iterations, also never re-synchronised.
 Whole-slab bit-exactness on skipped iterations is checked with device-side checksums.
 Each iteration is its own test so that no single test runs for minutes."""
 import concurrent.futures as cf
@@ -20,8 +27,9 @@ import torch
 
 import oracle
 import synthdata
-from _harness import (N_THREADS, compare_state, cpu_chunk_grad, cpu_chunk_state, download, fill_device_chunk,
-                      oracle_hp, oracle_sumsq_over_chunks, stream_handle, upload)
+from _harness import (N_THREADS, FreeRun, StepCtx, compare_state, cpu_chunk_grad, cpu_chunk_state, download,
+                      download_pinned, fill_device_chunk, oracle_hp, oracle_sumsq_over_chunks, resync, stream_handle,
+                      bit_view)
 from paper_2503_01890_amd import binding as B
 from paper_2503_01890_amd.modeldata import ModelData, STREAMS
 
@@ -83,9 +91,26 @@ class Run:
             self.sample = sorted(set(picks))
         with cf.ThreadPoolExecutor(N_THREADS) as ex:
             self.host = dict(zip(self.sample, ex.map(lambda c: cpu_chunk_state(w, c), self.sample)))
-        # one sampled chunk (not the first or last) is never re-synchronised: it drifts freely
-        mid = [c for c in self.sample if c not in (0, w.n_resident - 1)]
-        self.free = mid[len(mid) // 2] if (mid and w.steps > 1) else None
+        # the two never re-synchronised copies of the sampled chunks (their descriptors read the
+        # gradients of the main copy: gradients are read-only)
+        self.shadows = not self.variant
+        if self.shadows:
+            k = len(self.sample)
+            self.free_md, self.exact_md = ModelData([self.C] * k), ModelData([self.C] * k)
+            for md in (self.free_md, self.exact_md):
+                for j, c in enumerate(self.sample):
+                    st = stream_handle()
+                    synthdata.fill_gpu(md.ptr("param_lp", j), self.C, w.spec_param_lp(c), st)
+                    synthdata.fill_gpu(md.ptr("master", j), self.C, w.spec_master(c), st)
+                    synthdata.fill_gpu(md.ptr("exp_avg", j), self.C, w.spec_exp_avg(c), st)
+                    synthdata.fill_gpu(md.ptr("exp_avg_sq", j), self.C, w.spec_exp_avg_sq(c), st)
+            shadow = lambda md: B.chunk_array([(self.md.ptr("grad", c),) + md.chunk_tuple(j)[1:]
+                                               for j, c in enumerate(self.sample)])
+            self.free_arr, self.exact_arr = shadow(self.free_md), shadow(self.exact_md)
+            self.ws_exact = B.Workspace(k + 2)
+            self.ws_exact.tune(B.AH_TUNE_STEP_VARIANT, B.step_variant(4, 64, 1))
+            self.free_bound = {c: FreeRun(self.C) for c in self.sample}
+            self.free_stats = []
         self.t = 1                      # next AdamW step number (advances on non-skipped iterations)
         self.scale = w.loss_scale       # dynamic loss scale: halves after an overflow
         self.done = 0
@@ -116,62 +141,84 @@ class Run:
             extra = float(np.float32(s))
         hp = B.hparams(**w.hparams, loss_scale=scale)
         before = self.checksums() if it in w.inject else None
+        st = stream_handle()
         if self.carry:
             cur, nxt = (self.ws_other, self.ws) if it % 2 else (self.ws, self.ws_other)
-            nxt.autohete_grad_result_set(0.0, 0, stream_handle())
+            nxt.autohete_grad_result_set(0.0, 0, st)
             for arr, k in self.parts:
-                cur.autohete_adamw_step_carry(nxt, arr, k, w.dtype, self.t, hp, stream_handle())
-            _, gn, gf = nxt.autohete_grad_result_get(stream_handle())
+                cur.autohete_adamw_step_carry(nxt, arr, k, w.dtype, self.t, hp, st)
+            gs, gn, gf = nxt.autohete_grad_result_get(st)
         else:
-            gn, gf = self.ws.autohete_grad_prep(self.arr, w.n_resident, w.dtype, scale, extra, stream_handle(),
-                                                want_result=True)
+            self.ws.autohete_grad_prep(self.arr, w.n_resident, w.dtype, scale, extra, st)
+            gs, gn, gf = self.ws.autohete_grad_result_get(st)
         if self.split:
-            self.ws.autohete_adamw_step_master(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
-            self.ws.autohete_cast_params(self.arr, w.n_resident, w.dtype, stream_handle())
+            self.ws.autohete_adamw_step_master(self.arr, w.n_resident, w.dtype, self.t, hp, st)
+            self.ws.autohete_cast_params(self.arr, w.n_resident, w.dtype, st)
         elif not self.carry:
-            self.ws.autohete_adamw_step(self.arr, w.n_resident, w.dtype, self.t, hp, stream_handle())
-        torch.cuda.synchronize()
-        # oracle: norm over every resident chunk, then the sampled chunks element by element
+            self.ws.autohete_adamw_step(self.arr, w.n_resident, w.dtype, self.t, hp, st)
+        if self.shadows:       # the free-running copy: same kernel, same norm (still in the workspace)
+            self.ws.autohete_adamw_step(self.free_arr, len(self.sample), w.dtype, self.t, hp, st)
+        # oracle: norm over every resident chunk (runs while the GPU works), then the sampled chunks
         s, f = oracle_sumsq_over_chunks(w, range(w.n_resident), it, scale, patch)
         on, of = oracle.grad_finish(s + extra, f)
+        if self.shadows:       # the exact-mode copy is handed the ORACLE's sum of squares and flag
+            self.ws_exact.autohete_grad_result_set(s + extra, of, st)
+            self.ws_exact.autohete_adamw_step(self.exact_arr, len(self.sample), w.dtype, self.t, hp, st)
+        torch.cuda.synchronize()
         assert gf == of, (it, gf, of)
         assert of == (1 if it in w.inject else 0)
         if of:
             assert self.checksums() == before, "a skipped step must leave every stream bit-identical"
         else:
             assert abs(gn - on) <= 1e-5 * on, (it, gn, on)
-        def oracle_step(c):          # oracle update of one chunk, then its comparison with the device's;
-                                     # runs in a worker thread (the C calls and numpy release the GIL)
+        used_norm = self.prev_norm if self.carry else on      # carry: the norm of the previous iteration
+        ctx = StepCtx(w.dtype, hp, self.t, used_norm, None if (self.carry or of) else gs)
+        F32 = ("param_lp", "master", "exp_avg", "exp_avg_sq")
+
+        def oracle_step(j):          # oracle update of one chunk, then its comparison with the device's three
+            c = self.sample[j]       # copies; runs in a worker thread (the C calls and numpy release the GIL)
             g = cpu_chunk_grad(w, c, it, scale)
             for (pc, pi), bits in patch.items():
                 if pc == c:
                     g[pi] = bits
             h = self.host[c]
+            h["grad"] = g
             old = dict(master=h["master"].copy(), exp_avg=h["exp_avg"].copy(), exp_avg_sq=h["exp_avg_sq"].copy())
             if self.split:
                 oracle.adamw_chunk(g, None, h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
                                    oracle_hp(hp), on, of)
                 if not of:
                     oracle.cast_chunk(h["master"], h["param_lp"], w.dtype)
-            elif self.carry:     # the norm of the previous iteration (none before the first)
-                oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
-                                   oracle_hp(hp), self.prev_norm, 0)
             else:
                 oracle.adamw_chunk(g, h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
-                                   oracle_hp(hp), on, of)
-            got = download(md, c, ("param_lp", "master", "exp_avg", "exp_avg_sq"))
-            st = compare_state(got, h, "%s it=%d chunk=%d" % (w.name, it, c), old,
-                               drift_steps=(self.t - 1 if c == self.free else 0))
-            st.update(it=it, chunk=c)
-            return st
+                                   oracle_hp(hp), used_norm, 0 if self.carry else of)
+            where = "%s it=%d chunk=%d" % (w.name, it, c)
+            got = download_pinned(md, c, F32)
+            stats = compare_state(got, h, where, None if of else old, ctx)
+            stats.update(it=it, chunk=c)
+            if any(stats[k + "_mismatch"] for k in F32):
+                resync(md, c, got, h, F32)                 # oracle -> device: the next step starts identical
+            free = None
+            if self.shadows:
+                got = download_pinned(self.exact_md, j, F32)
+                for k in F32:
+                    assert np.array_equal(bit_view(got[k]), bit_view(h[k])), (where, k, "exact mode with the oracle's norm "
+                                                                      "is not bit-identical to the oracle")
+                got = download_pinned(self.free_md, j, F32)
+                if of:                                         # skipped: nothing moves on either side
+                    free = compare_free_skip(got, h, self.free_bound[c], where)
+                else:
+                    free = self.free_bound[c].step(got, h, old, ctx, where + " (free-running)")
+                    free.update(it=it, chunk=c)
+            del h["grad"]
+            return stats, free
 
         with cf.ThreadPoolExecutor(min(N_THREADS, len(self.sample))) as ex:
-            results = list(ex.map(oracle_step, self.sample))       # a failed comparison is raised here
-        for c, st in zip(self.sample, results):
-            self.stats.append(st)
-            if c != self.free and not of and any(st[k] for k in ("master_mismatch", "exp_avg_mismatch",
-                                                                  "exp_avg_sq_mismatch", "param_lp_mismatch")):
-                upload(md, c, self.host[c])          # oracle -> device: next step starts identical
+            results = list(ex.map(oracle_step, range(len(self.sample))))       # a failed comparison is raised here
+        for stats, free in results:
+            self.stats.append(stats)
+            if free:
+                self.free_stats.append(free)
         if of:
             self.scale = scale / 2.0
         else:
@@ -187,23 +234,53 @@ class Run:
             last = download(self.md, w.n_chunks - 1)
             for s in STREAMS:
                 assert not last[s][-n_pad:].view(np.uint8).any(), "padding must stay +0 (%s)" % s
-        n = sum(s["n"] for s in self.stats)
-        worst = {k: max(s[k] for s in self.stats) for k in ("master_max_ulp", "exp_avg_max_ulp",
-                                                             "exp_avg_sq_max_ulp", "param_lp_max_ulp")}
-        mism = {k: sum(s[k] for s in self.stats) for k in ("master_mismatch", "exp_avg_mismatch",
-                                                            "exp_avg_sq_mismatch", "param_lp_mismatch",
-                                                            "master_relaxed", "exp_avg_relaxed", "exp_avg_sq_relaxed")}
+        F32 = ("master", "exp_avg", "exp_avg_sq")
         out_dir = os.environ.get("AUTOHETE_PARITY_REPORT_DIR", "parity_reports")
         os.makedirs(out_dir, exist_ok=True)
         with open(os.path.join(out_dir, "parity_%s%s.txt" % (w.name, "_" + self.variant if self.variant else "")), "w") as fh:
-            fh.write("workload %s: %d iterations, %d updates, sampled chunks %s (free-running: %s)\n" %
-                     (w.name, self.done, self.t - 1, self.sample, self.free))
-            fh.write("element-steps compared: %d\nworst error vs oracle (ulp, cancelled elements aside): %s\n"
-                     "bitwise mismatches / elements judged with the cancellation or drift allowance: %s\n" %
-                     (n, worst, mism))
+            fh.write("workload %s: %d iterations, %d updates, sampled chunks %s\n" %
+                     (w.name, self.done, self.t - 1, self.sample))
+            fh.write("main copy (re-synchronised with the oracle after every iteration; strict rule)\n")
+            fh.write("  element-steps compared: %d\n" % sum(s["n"] for s in self.stats))
+            for k in F32:
+                fh.write("  %-10s bitwise mismatches %d; worst error %.2f ulp32(result) / %.3f ulp32(T); judged "
+                         "by the largest-term arm: %d\n" %
+                         (k, sum(s[k + "_mismatch"] for s in self.stats), max(s[k + "_max_ulp"] for s in self.stats),
+                          max(s[k + "_max_ulp_T"] for s in self.stats), sum(s[k + "_beyond"] for s in self.stats)))
+            fh.write("  param_lp   bitwise mismatches %d; worst %d ulp16\n" %
+                     (sum(s["param_lp_mismatch"] for s in self.stats), max(s["param_lp_max_ulp"] for s in self.stats)))
+            if self.shadows and self.free_stats:
+                last = [s for s in self.free_stats if s["it"] == max(x["it"] for x in self.free_stats)]
+                fh.write("free-running copy (default kernel, never re-synchronised, %d updates)\n" % (self.t - 1))
+                for k in F32:
+                    # r.m.s. magnitude of the stream (oracle side, last update): what "one ulp" means for it
+                    rms = float(np.sqrt(sum(s[k + "_sumsq_ora"] for s in last) / sum(s["n"] for s in last)))
+                    fh.write("  %-10s after the last update: %d of %d elements differ from the oracle, %d beyond 2 ulp32 / "
+                             "1e-6 of their own value; over all updates: largest error %.3g = %.2f ulp32 of the stream's "
+                             "r.m.s. magnitude %.3g, %.2f ulp32(T) of its own largest term, %.3f of the bound E it was "
+                             "held to\n" %
+                             (k, sum(s[k + "_mismatch"] for s in last), sum(s["n"] for s in last),
+                              sum(s[k + "_beyond"] for s in last), max(s[k + "_max_abs"] for s in self.free_stats),
+                              max(s[k + "_max_abs"] for s in self.free_stats) / float(np.spacing(np.float32(rms))), rms,
+                              max(s[k + "_max_ulp_T"] for s in self.free_stats),
+                              max(s[k + "_max_E_frac"] for s in self.free_stats)))
+                fh.write("  param_lp   after the last update: %d differ; worst %d ulp16\n" %
+                         (sum(s["param_lp_mismatch"] for s in last), max(s["param_lp_max_ulp"] for s in self.free_stats)))
+                fh.write("exact-mode copy (oracle's sum of squares handed in, never re-synchronised): bit-identical to "
+                         "the oracle in all four streams of every sampled chunk after every iteration\n")
         self.ws.close()
         if self.carry:
             self.ws_other.close()
+        if self.shadows:
+            self.ws_exact.close()
+
+
+def compare_free_skip(got, h, bound, where):
+    """A skipped iteration leaves both sides where they were: the bound carried so far still holds."""
+    for k in ("master", "exp_avg", "exp_avg_sq"):
+        err = np.abs(got[k].astype(np.float64) - h[k].astype(np.float64))
+        assert np.all(err <= bound.D[k]), (where, k, "free-running copy moved on a skipped step")
+    return None
 
 
 _runs = {}
@@ -327,4 +404,96 @@ def test_every_byte_agrees_between_kernel_variants_at_model_scale(name, iteratio
     for x in ws + [carried]:
         x.close()
     del copies
+    torch.cuda.empty_cache()
+
+
+def test_hybrid_placement_at_full_size_both_halves_against_the_oracle():
+    """The 13B configuration end to end: 192 chunks updated by the GPU kernels, 192 by the library's
+    host optimizer (gradients D2H -> host AdamW -> 16-bit parameters H2D, pipelined), two steps.
+    The oracle replays 8 resident and 8 host-owned chunks element by element (first, last and
+    seeded random ones of each half) under the strict rule, and the global norm over all 384
+    chunks; after the first step the oracle's state of those chunks is written over both halves."""
+    from paper_2503_01890_amd.hybrid import HostChunks, HybridStepper
+    for r in _runs.values():
+        r.md = None
+    _runs.clear()
+    torch.cuda.empty_cache()
+    w = synthdata.workload("gpt-13b-half-resident")
+    C, n_res, n_host = w.chunk_elems, w.n_resident, w.n_chunks - w.n_resident
+    st = stream_handle()
+    md = ModelData([C] * n_res)
+    for c in range(n_res):
+        fill_device_chunk(md, w, c)
+    host = HostChunks(n_host, C)
+
+    def init_host(c):
+        synthdata.fill_cpu(host.master[c], w.spec_master(n_res + c))
+        synthdata.fill_cpu(host.exp_avg[c], w.spec_exp_avg(n_res + c))
+        synthdata.fill_cpu(host.exp_avg_sq[c], w.spec_exp_avg_sq(n_res + c))
+
+    with cf.ThreadPoolExecutor(N_THREADS) as ex:
+        list(ex.map(init_host, range(n_host)))
+    for c in range(n_host):
+        synthdata.fill_gpu(host.dev_view("param_lp", c).data_ptr(), C, w.spec_param_lp(n_res + c), st)
+    rng = np.random.default_rng(99)
+    pick = lambda lo, n: sorted({lo, lo + n - 1} | {int(x) for x in lo + rng.choice(np.arange(1, n - 1), 6, replace=False)})
+    sample = pick(0, n_res) + pick(n_res, n_host)
+    assert len(sample) == 16
+    with cf.ThreadPoolExecutor(N_THREADS) as ex:
+        ora = dict(zip(sample, ex.map(lambda c: cpu_chunk_state(w, c), sample)))
+    stepper = HybridStepper(md, host, w.dtype, N_THREADS)
+    hp = B.hparams(**w.hparams, loss_scale=w.loss_scale)
+    F32 = ("param_lp", "master", "exp_avg", "exp_avg_sq")
+    report = []
+    for it in (1, 2):
+        for c in range(n_res):
+            fill_device_chunk(md, w, c, iteration=it, state=False)
+        for c in range(n_host):
+            synthdata.fill_gpu(host.dev_view("grad", c).data_ptr(), C, w.spec_grad(n_res + c, it), st)
+        torch.cuda.synchronize()
+        out = stepper.step(it, hp)
+        s, f = oracle_sumsq_over_chunks(w, range(w.n_chunks), it, w.loss_scale)
+        on, of = oracle.grad_finish(s, f)
+        assert out["found_inf"] == of == 0 and abs(out["norm"] - on) <= 1e-5 * on
+        ctx = StepCtx(w.dtype, hp, it, on, out["sumsq"])
+
+        def one(c):
+            h = ora[c]
+            h["grad"] = cpu_chunk_grad(w, c, it)
+            old = dict(master=h["master"].copy(), exp_avg=h["exp_avg"].copy(), exp_avg_sq=h["exp_avg_sq"].copy())
+            oracle.adamw_chunk(h["grad"], h["param_lp"], h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, it,
+                               oracle_hp(hp), on, of)
+            if c < n_res:
+                got = download_pinned(md, c, F32)
+            else:
+                k = c - n_res
+                got = dict(master=host.master[k], exp_avg=host.exp_avg[k], exp_avg_sq=host.exp_avg_sq[k],
+                           param_lp=host.dev_view("param_lp", k).cpu().numpy().view(np.uint16))
+            stats = compare_state(got, h, "hybrid it=%d chunk=%d (%s)" % (it, c, "GPU" if c < n_res else "host"), old, ctx)
+            if c < n_res:
+                resync(md, c, got, h, F32)
+            else:
+                k = c - n_res
+                host.master[k][:], host.exp_avg[k][:], host.exp_avg_sq[k][:] = h["master"], h["exp_avg"], h["exp_avg_sq"]
+                host.dev_view("param_lp", k).copy_(torch.from_numpy(h["param_lp"].view(np.int16)))
+            del h["grad"]
+            return c, stats
+
+        with cf.ThreadPoolExecutor(min(N_THREADS, len(sample))) as ex:
+            report += [(it,) + r for r in ex.map(one, sample)]
+    stepper.close()
+    out_dir = os.environ.get("AUTOHETE_PARITY_REPORT_DIR", "parity_reports")
+    os.makedirs(out_dir, exist_ok=True)
+    with open(os.path.join(out_dir, "parity_gpt-13b-half-resident_hybrid.txt"), "w") as fh:
+        fh.write("hybrid placement, 2 steps, chunks %s (resident below %d, host-owned from there)\n" % (sample, n_res))
+        for half, keep in (("GPU half ", lambda c: c < n_res), ("host half", lambda c: c >= n_res)):
+            rows = [s for (_, c, s) in report if keep(c)]
+            fh.write("%s: %d element-steps; bitwise mismatches m/v/p/p16 %d/%d/%d/%d; worst %.2f/%.2f/%.2f ulp32(result); "
+                     "judged by the largest-term arm: %d\n" %
+                     (half, sum(s["n"] for s in rows), sum(s["exp_avg_mismatch"] for s in rows),
+                      sum(s["exp_avg_sq_mismatch"] for s in rows), sum(s["master_mismatch"] for s in rows),
+                      sum(s["param_lp_mismatch"] for s in rows), max(s["exp_avg_max_ulp"] for s in rows),
+                      max(s["exp_avg_sq_max_ulp"] for s in rows), max(s["master_max_ulp"] for s in rows),
+                      sum(s["exp_avg_beyond"] + s["master_beyond"] for s in rows)))
+    del md, host, stepper
     torch.cuda.empty_cache()
