@@ -31,6 +31,11 @@ def test_oracle_points_evaluated_by_hand():
     #   GPU = 0 + 60 + 2*100*1 + 0 + 50 = 310;  T_bwd = max(4 + 0 + 0 + 4, 2 + 0.5 + 6) = 8.5
     s = so.evaluate(HAND, 0, 2, 2)
     assert (s["gpu"], s["t_sync"], s["t_bwd"]) == (310, 4, 8.5)
+    # (2, 0, 0): both blocks recomputed, everything on the GPU: the GPU arm of Eq. 5 decides
+    #   GPU = 2*2*2 + 2*10*1 + 2*100*3 + 12*100*2 + 50 = 3078
+    #   T_bwd = max(2*2 + 1*2 + 0.25*2 + 0, 2 + 0.5 + 0) = max(6.5, 2.5) = 6.5
+    s = so.evaluate(HAND, 2, 0, 0)
+    assert (s["gpu"], s["t_sync"], s["t_bwd"]) == (3078, 0, 6.5)
     # p > o is not a strategy (footnote to the peak-memory model)
     assert not so.evaluate(HAND, 0, 2, 1)["feasible"]
     # the example of the paper's scheduling figure: L = 5, c = 3, p = 1, o = 5 -> one block has both
@@ -129,3 +134,74 @@ def test_measured_gpu_optimizer_cost_moves_the_plan():
     assert small.t_fwd + small.t_bwd > plenty.t_fwd + plenty.t_bwd
     ref = so.search(dict(base, Mgpu=80e9))
     assert (small.n_ckpt, small.n_param_offload, small.n_optim_offload) == (ref["c"], ref["p"], ref["o"])
+
+
+def test_ties_go_to_the_least_offloading_by_hand():
+    """Eq. 6 does not say which of several equally fast strategies to take; the reading (least
+    optimizer offloading, then least parameter offloading, then least checkpointing) is pinned on a
+    model whose ties are evaluated by hand.  L = 2, t_fp = 1, t_bp = 2, a free GPU optimizer
+    (t_optim_gpu = 0), a host optimizer and copies that hide under the backward pass:
+      T_fwd = max(2, 0.5 o + 1) = 2 for every o;  t_sync = 0 (t_h2d < t_bp);
+      T_bwd = max(4 + c, 2 + 0.1 + 0.5 o) = 4 + c  ->  T = 6 for every (0, p, o): six-fold tie."""
+    m = dict(HAND, tgpu=0.0, th2d=0.5, td2h=0.1, tcpu=0.5)
+    for o in range(3):
+        for p in range(o + 1):
+            s = so.evaluate(m, 0, p, o)
+            assert s["feasible"] and s["t_fwd"] + s["t_bwd"] == 6.0
+    best = so.search(m)
+    assert (best["c"], best["p"], best["o"]) == (0, 0, 0)
+    got = B.autohete_strategy_search(to_c(m))
+    assert (got.n_ckpt, got.n_param_offload, got.n_optim_offload) == (0, 0, 0)
+    # memory that only fits with one block's optimizer states on the host AND one block's parameters
+    # offloaded: Eq. 1 at (0, 1, 1) = 2*10*3 + 2*100*2 + 12*100*1 + 50 = 1710, at (0, 0, 1) = 1910
+    tight = dict(m, Mgpu=1800)
+    assert so.evaluate(tight, 0, 1, 1)["gpu"] == 1710 and so.evaluate(tight, 0, 0, 1)["gpu"] == 1910
+    # feasible and tied at T = 6: (0,1,1), (0,1,2), (0,2,2), (0,0,2) [1310 bytes] -> smallest o wins, then p
+    best = so.search(tight)
+    assert (best["c"], best["p"], best["o"]) == (0, 1, 1)
+    got = B.autohete_strategy_search(to_c(tight))
+    assert (got.n_ckpt, got.n_param_offload, got.n_optim_offload) == (0, 1, 1)
+
+
+STRATEGY_MUTATIONS = {
+    "v_is_max_not_min": ("v = min(c, p)", "v = max(c, p)"),
+    "no_plus_one_activation": ("2 * m[\"Ma\"] * (L - c + 1)", "2 * m[\"Ma\"] * (L - c)"),
+    "no_plus_one_parameter": ("2 * m[\"Mp\"] * (L - p + 1)", "2 * m[\"Mp\"] * (L - p)"),
+    "states_12_vs_14": ("12 * m[\"Mp\"] * (L - o)", "14 * m[\"Mp\"] * (L - o)"),
+    "host_14_vs_12": ("14 * m[\"Mp\"] * o", "12 * m[\"Mp\"] * o"),
+    "checkpoint_keeps_all": ("2 * m[\"Ma1\"] * c ", "2 * m[\"Ma\"] * c "),
+    "fwd_forgets_last_compute": ("m[\"th2d\"] * o + m[\"tfp\"])", "m[\"th2d\"] * o)"),
+    "sync_ignores_recompute": ("max(m[\"th2d\"] - m[\"tfp\"] - m[\"tbp\"], 0)", "max(m[\"th2d\"] - m[\"tbp\"], 0)"),
+    "bwd_no_recompute_time": ("+ m[\"tfp\"] * c + m[\"tgpu\"]", "+ m[\"tgpu\"]"),
+    "gpu_optim_counts_offloaded": ("m[\"tgpu\"] * (L - o)", "m[\"tgpu\"] * o"),
+    "cpu_path_without_d2h": ("m[\"tbp\"] + m[\"td2h\"] + m[\"tcpu\"] * o", "m[\"tbp\"] + m[\"tcpu\"] * o"),
+    "bwd_sum_not_max": ("t_bwd = max(on_gpu, on_cpu)", "t_bwd = on_gpu + on_cpu"),
+    "p_le_o_dropped": ("and cpu <= m[\"Mcpu\"] and p <= o", "and cpu <= m[\"Mcpu\"]"),
+    "cpu_limit_dropped": ("gpu <= m[\"Mgpu\"] and cpu <= m[\"Mcpu\"]", "gpu <= m[\"Mgpu\"]"),
+    "gpu_constant_dropped": ("    gpu += m[\"Mgc\"] ", "    gpu += 0 "),
+    "tie_prefers_last": ("< best[\"t_fwd\"] + best[\"t_bwd\"]", "<= best[\"t_fwd\"] + best[\"t_bwd\"]"),
+    "search_skips_full_offload": ("for o in range(L + 1):", "for o in range(L):"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(STRATEGY_MUTATIONS))
+def test_planted_mistake_in_the_strategy_oracle_is_caught(name, monkeypatch):
+    """Each case plants one plausible mistake in a copy of the strategy oracle's source and requires
+    that one of the hand-evaluated pins above fails against it."""
+    import types
+    old, new = STRATEGY_MUTATIONS[name]
+    text = open(so.__file__).read()
+    assert text.count(old) == 1, name
+    mutant = types.ModuleType("strategy_mutant")
+    exec(compile(text.replace(old, new), "strategy_mutant.py", "exec"), mutant.__dict__)
+    monkeypatch.setattr(so, "evaluate", mutant.evaluate)
+    monkeypatch.setattr(so, "search", mutant.search)
+    caught = False
+    for pin in (test_oracle_points_evaluated_by_hand, test_oracle_search_properties,
+                test_ties_go_to_the_least_offloading_by_hand):
+        try:
+            pin()
+        except (AssertionError, TypeError, KeyError):
+            caught = True
+            break
+    assert caught, "mutation %r survived every pin" % name
