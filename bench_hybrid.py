@@ -28,6 +28,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--host-chunks", type=int, default=0, help="host-owned chunks to run (0 = all of the workload's)")
     ap.add_argument("--threads", type=int, default=0, help="host optimizer threads (0 = the box's CPU share)")
+    ap.add_argument("--plan", action="store_true",
+                    help="also time a plain streaming pass on the host threads, measure a synthetic transformer "
+                         "block's GEMMs, and feed all measured costs to autohete_strategy_search")
     args = ap.parse_args()
 
     import numpy as np
@@ -113,7 +116,86 @@ def main():
         "grad_norm": runs[-1]["norm"],
     }
     stepper.close()
+    if args.plan:
+        del md, host, stepper
+        torch.cuda.empty_cache()
+        out["host_streaming_roofline"] = host_stream_rate(threads)
+        out["plan"] = plan(w, out["cost_model_inputs_per_block"], args)
     print(json.dumps(out))
+
+
+def host_stream_rate(threads, log2_elems=27):
+    """What the same host threads reach on a plain streaming pass with the update's traffic (per
+    element: 2 + 12 bytes read, 12 + 2 written) and no arithmetic beyond copies: the roofline the
+    host optimizer's rate is read against."""
+    import concurrent.futures as cf
+    import numpy as np
+    n = 1 << log2_elems
+    per = n // threads
+    src = [np.ones(per, np.float32) for _ in range(threads)]
+    dst = [[np.empty(per, np.float32) for _ in range(3)] for _ in range(threads)]
+    g = [np.ones(per, np.uint16) for _ in range(threads)]
+
+    def work(t):
+        for k in range(3):
+            np.copyto(dst[t][k], src[t])          # 4 B read + 4 B written, three streams
+        np.copyto(g[t], g[t])                     # 2 B read + 2 B written
+    with cf.ThreadPoolExecutor(threads) as ex:
+        list(ex.map(work, range(threads)))
+        t0 = time.perf_counter()
+        for _ in range(3):
+            list(ex.map(work, range(threads)))
+        dt = (time.perf_counter() - t0) / 3
+    return {"GBps": 28.0 * per * threads / dt / 1e9, "params_per_s": per * threads / dt, "threads": threads,
+            "what": "numpy copies of three fp32 streams and one 16-bit stream, %d elements per thread" % per}
+
+
+def plan(w, per_block, args):
+    """Feeds the costs measured above into the library's cost model and strategy search (paper Eq. 1-6)
+    for this workload's transformer block.  t_fp / t_bp are measured on the block's four bf16 weight
+    GEMMs at the paper's batch (8 sequences of 1024 tokens; attention scores left out), activations
+    are taken as 17 b s d elements per block (34 b s d bytes in 16 bits) with b s d kept by a
+    checkpointed block: stand-ins for what a profiler of a real model would supply."""
+    import torch
+    from paper_2503_01890_amd import binding as B
+    d = {"gpt-13b-half-resident": 5120, "gpt-6.7b": 4096, "gpt-1.3b": 2048, "gpt-124m": 768}[w.name]
+    n_layers = (len(w.tensor_numel) - 2) // 12
+    tokens = 8 * 1024
+    x = torch.randn(tokens, d, device="cuda:0", dtype=torch.bfloat16)
+    x4 = torch.randn(tokens, 4 * d, device="cuda:0", dtype=torch.bfloat16)
+    ws_ = [torch.randn(d, k * d, device="cuda:0", dtype=torch.bfloat16) for k in (3, 1, 4)]
+    w_down = torch.randn(4 * d, d, device="cuda:0", dtype=torch.bfloat16)
+
+    def fwd():
+        for m in ws_:
+            torch.matmul(x, m)
+        torch.matmul(x4, w_down)
+    for _ in range(3):
+        fwd()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        fwd()
+    torch.cuda.synchronize()
+    t_fp = (time.perf_counter() - t0) / 10
+    host_ram = os.sysconf("SC_PAGE_SIZE") * os.sysconf("SC_PHYS_PAGES")
+    block = per_block["block_params"]
+    model = dict(n_blocks=n_layers, act_elems=17.0 * tokens * d, act_in_elems=1.0 * tokens * d, param_elems=float(block),
+                 gpu_const_bytes=2.0 * 16 * float(w.tensor_numel[0] + w.tensor_numel[1]) + 2e9, cpu_const_bytes=2e9,
+                 gpu_capacity_bytes=288e9, cpu_capacity_bytes=float(host_ram), t_fp=t_fp, t_bp=2 * t_fp,
+                 t_h2d=per_block["t_h2d_s"], t_d2h=per_block["t_d2h_s"], t_optim_cpu=per_block["t_optim_cpu_s"],
+                 t_optim_gpu=per_block["t_optim_gpu_s"])
+    res = {"inputs": model}
+    for name, cap in (("mi355x_288GB", 288e9), ("gpu_80GB", 80e9), ("gpu_40GB", 40e9)):
+        cm = B.autohete_cost_model(**dict(model, gpu_capacity_bytes=cap))
+        try:
+            s = B.autohete_strategy_search(cm)
+            res[name] = {"ckpt_blocks": s.n_ckpt, "param_offload_blocks": s.n_param_offload,
+                         "optim_offload_blocks": s.n_optim_offload, "eq1_gpu_bytes": s.gpu_bytes,
+                         "eq2_cpu_bytes": s.cpu_bytes, "t_fwd_s": s.t_fwd, "t_sync_s": s.t_sync, "t_bwd_s": s.t_bwd}
+        except B.AutoheteError as e:
+            res[name] = {"infeasible": str(e)}
+    return res
 
 
 if __name__ == "__main__":

@@ -157,6 +157,16 @@ class Workload:
         return self._spec(STREAM_GRAD, iteration, chunk, 1e-3 * s, OUT_LOWP,
                           outlier_prob=self.outlier_prob, sigma_outlier=1.0 * s)
 
+    def partition_bounds(self):
+        """Flat element bounds of the optimizer partitions of a GPT-shaped workload: the embedding
+        tables, then one partition per transformer block (12 tensors each); the last one also
+        takes the padding of the last chunk.  -> [0, b1, ..., n_chunks * chunk_elems]"""
+        off = np.concatenate([[0], np.cumsum(self.tensor_numel.astype(np.int64))])
+        n_layers, rest = divmod(len(self.tensor_numel) - 2, 12)
+        assert rest == 0 and n_layers > 0, "not a GPT-shaped tensor list"
+        bounds = [0] + [int(off[2 + 12 * i]) for i in range(n_layers)] + [self.n_chunks * self.chunk_elems]
+        return bounds
+
     def inject_index(self, iteration):
         """Flat element (within the resident chunks) that is overwritten at `iteration`."""
         k = _cpu_lib().synth_cpu_key(self.seed, STREAM_MISC, iteration)
