@@ -69,9 +69,21 @@ namespace {
 /* Encoding of AH_TUNE_STEP_VARIANT: vec | mode << 4 | (block / 64) << 8.
  * Default: 4 elements per lane, one wavefront per block, Newton fp64, at most 10 blocks per CU. */
 constexpr int64_t kDefaultVariant = 4 | (0 << 4) | (1 << 8);
-constexpr int kDefaultBlocksPerCu = 10;
-constexpr int kDefaultMasterBlocksPerCu = 12; /* no 16-bit store: 10 -> 80.4, 11 -> 82.2, 12 -> 83.0, 14 -> 81.5 % of peak */
-constexpr int kDefaultCarryBlocksPerCu = 11; /* its waves live a little longer: 10 -> 28.9, 11 -> 28.5, 14 -> 29.0 ms */
+/* Default cap on resident update blocks per CU, by the elements one call covers.  The steady state
+ * of a long launch is fastest at 10 (6.7 G elements: 9 -> 82.2, 10 -> 82.1, 11 -> 81.7, 12 -> 80.9 % of
+ * peak); in shorter launches the ramp and the tail weigh more and one or two more resident waves pay
+ * (1.3 G elements: 10 -> 82.3, 11 -> 83.2, 12 -> 82.8, 13 -> 81.9; 2.7 G: 10 -> 82.2, 11 -> 83.1,
+ * 12 -> 82.7; 0.13 G: 8 -> 80.2, 10 -> 82.5, 12 -> 83.7, 14 -> 81.4, 16 -> 80.2). */
+int default_blocks_per_cu(uint64_t call_elems)
+{
+    return call_elems < (1ull << 29) ? 12 : call_elems < (1ull << 32) ? 11 : 10;
+}
+/* The update without the 16-bit store (6.7 G elements: 10 -> 80.4, 11 -> 82.2, 12 -> 83.0, 14 -> 81.5). */
+constexpr int kDefaultMasterBlocksPerCu = 12;
+/* The norm-carrying update: its waves live a little longer, one more than the plain update, at most 12
+ * (6.7 G elements in one call: 10 -> 28.9, 11 -> 28.5, 14 -> 29.0 ms; one transformer block (0.2 G) per
+ * call: 10 -> 76.7, 11 -> 80.0, 12 -> 80.6, 13 -> 80.3, 14 -> 79.3 % of peak). */
+int default_carry_blocks_per_cu(uint64_t call_elems) { return std::min(default_blocks_per_cu(call_elems) + 1, 12); }
 constexpr int kDefaultCastBlocksPerCu = 24; /* measured: 64 -> 6.38, 24 -> 6.88, 16 -> 6.10 TB/s */
 
 bool decode_variant(int64_t v, ah::StepVariant *out)
@@ -637,9 +649,10 @@ static int step_common(autohete_ws *ws, const autohete_chunk *chunks, uint64_t n
     k.eps = (double)hp->eps;
     k.wd = (double)hp->weight_decay;
 
+    const uint64_t call_elems = tab->tiles * (uint64_t)(var.vec * var.block);
     const unsigned lds = lds_for_cap(ws, ws->tune_step_blocks_per_cu ? ws->tune_step_blocks_per_cu
-                                         : carry_to ? kDefaultCarryBlocksPerCu
-                                         : write_back ? kDefaultBlocksPerCu : kDefaultMasterBlocksPerCu);
+                                         : carry_to ? default_carry_blocks_per_cu(call_elems)
+                                         : write_back ? default_blocks_per_cu(call_elems) : kDefaultMasterBlocksPerCu);
     if (!carry_to) {
         for (const autohete_ws::Group &grp : tab->groups) {
             if (ah::launch_step(lowp_dtype, var, (unsigned)grp.max_tiles, grp.rows, lds, stream,
