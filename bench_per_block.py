@@ -77,6 +77,7 @@ def main():
     ws = [B.Workspace(n + 2), B.Workspace(n + 2)]
     for x in ws:
         x.tune(B.AH_TUNE_STEP_BLOCKS_PER_CU, args.blocks_per_cu)
+        x.tune(B.AH_TUNE_CARRY_ELEMS, n * C)
     whole = md.chunk_array()
     a_mat = torch.randn(args.gemm, args.gemm, device="cuda:0", dtype=torch.bfloat16)
     b_mat = torch.randn(args.gemm, args.gemm, device="cuda:0", dtype=torch.bfloat16)
