@@ -83,3 +83,19 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_header_is_valid_c99_and_a_plain_c_program_can_use_the_library(tmp_path):
+    """include/autohete.h under gcc -std=c99 -pedantic, then a C caller of the host-only entry
+    points (tests/c_abi_host.c) linked against libautohete.so and run."""
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c",
+                           os.path.join(inc, "autohete.h")])
+    libdir = os.path.dirname(B.LIB_PATH)
+    exe = str(tmp_path / "c_abi_host")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc,
+                           os.path.join(ROOT, "tests", "c_abi_host.c"), "-o", exe, "-L", libdir, "-l:libautohete.so",
+                           "-Wl,-rpath," + libdir, "-Wl,-rpath-link,/opt/rocm/lib", "-lm"])
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and "c abi host: ok" in run.stdout, (run.stdout, run.stderr[-2000:])
