@@ -110,3 +110,35 @@ def test_static_norm_pass_rejects_what_it_cannot_take():
     assert call(B.chunk_array([(g.data_ptr() + 2, None, None, None, None, 16)]), 1) == B.AH_EALIGN
     assert call(B.chunk_array([(g.data_ptr(), None, None, None, None, 0)]), 1) == B.AH_EINVAL
     assert B.raw().autohete_strerror(B.AH_ELIMIT).decode().startswith("more chunks")
+
+
+def test_static_norm_pass_recorded_into_a_hip_graph():
+    """The entry point makes no allocation and no memset node, so it can be recorded into a HIP
+    graph; four replays with eager work and synchronisations between them, each against the
+    workspace path on the same (changing) gradients."""
+    torch.cuda.set_device(0)
+    s = torch.cuda.current_stream().cuda_stream
+    sizes = [16384 * 9 + 11, 70_000, 16384 * 300]
+    dev, host, tuples = _grads(sizes, B.AH_BF16, seed=3, scale=1.0)
+    arr = B.chunk_array(tuples)
+    out = torch.zeros(32, dtype=torch.uint8, device="cuda:0")
+    ws = B.Workspace(4)
+    side = torch.cuda.Stream()                                     # default priority
+    with torch.cuda.stream(side):                                  # first call on the capture stream: looks up the array
+        B.autohete_grad_prep_static(arr, 3, B.AH_BF16, 1.0, 0.5, side.cuda_stream, out.data_ptr())
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        B.autohete_grad_prep_static(arr, 3, B.AH_BF16, 1.0, 0.5, side.cuda_stream, out.data_ptr())
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(12)
+    for rep in range(4):
+        dev[:4096] = torch.from_numpy(rng.integers(0, 0x3F80, 4096).astype(np.int16)).to(dev.device)   # eager work
+        out.fill_(0xEE)
+        torch.cuda.synchronize()
+        g.replay()
+        norm, flag = ws.autohete_grad_prep(arr, 3, B.AH_BF16, 1.0, 0.5, s, want_result=True)
+        torch.cuda.synchronize()
+        sumsq, norm_d, norm_f, found = _result(out)
+        assert (sumsq, norm_f, found) == (ws.autohete_grad_result_get(s)[0], norm, flag), rep
+    ws.close()
