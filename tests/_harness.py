@@ -154,7 +154,9 @@ class StepCtx:
     def __init__(self, dtype, hp, step, norm, sumsq_gpu=None):
         self.dtype, self.hp, self.step, self.norm = dtype, hp, int(step), float(norm)
         # rho: relative difference of the two sides' clip factors, known when the caller read the
-        # GPU's sum of squares (the oracle's is norm^2): <= half the relative difference of the sums
+        # GPU's sum of squares (the oracle's is norm^2).  The factor is max_norm / (sqrt(S) + 1e-6), so
+        # it differs by at most half the relative difference of the sums; the full difference is taken,
+        # plus 2^-50 for the few fp64 roundings (square root, sum, quotient) each side makes on the way.
         self.rho = None
         if sumsq_gpu is not None:
             s_o = self.norm * self.norm
