@@ -193,6 +193,13 @@ def _lowp(gpu, ora, where, stats):
     return stats
 
 
+def _grad_f32(ora, ctx):
+    """The chunk's 16-bit gradients decoded by the oracle; callers that compare several device copies
+    against one oracle state may leave the decoded array under "grad_f32" to have it decoded once."""
+    gf = ora.get("grad_f32")
+    return gf if gf is not None else oracle.decode(ora["grad"], ctx.dtype)
+
+
 def compare_state(gpu, ora, where="", old=None, ctx=None):
     """The parity bar for a step that both sides took from IDENTICAL inputs (tests/parity_check.c,
     parity_strict): fp32 master and moments within max(2 ulp32, relative 1e-6) of the oracle, or
@@ -203,7 +210,7 @@ def compare_state(gpu, ora, where="", old=None, ctx=None):
     third = old is not None and ctx is not None and "grad" in ora
     raw = (ctypes.c_double * (3 * len(PS_FIELDS)))()
     k = ctx.consts() if third else ParityConsts()
-    gf = oracle.decode(ora["grad"], ctx.dtype) if third else None
+    gf = _grad_f32(ora, ctx) if third else None
     _parity_lib().parity_strict(ora["master"].size, _fp(gf), _fp(old["exp_avg"]) if third else None,
                                 _fp(old["master"]) if third else None, _fp(ora["exp_avg"]), _fp(ora["exp_avg_sq"]),
                                 _fp(ora["master"]), _fp(gpu["exp_avg"]), _fp(gpu["exp_avg_sq"]), _fp(gpu["master"]),
@@ -236,7 +243,7 @@ class FreeRun:
         assert ctx.rho is not None, "the bound needs the GPU's sum of squares"
         k = ctx.consts(ctx.rho)
         raw = (ctypes.c_double * (3 * len(PS_FIELDS)))()
-        gf = oracle.decode(ora["grad"], ctx.dtype)
+        gf = _grad_f32(ora, ctx)
         _parity_lib().parity_free(ora["master"].size, _fp(gf), _fp(old["exp_avg"]), _fp(old["master"]),
                                   _fp(ora["exp_avg"]), _fp(ora["exp_avg_sq"]), _fp(ora["master"]),
                                   _fp(gpu["exp_avg"]), _fp(gpu["exp_avg_sq"]), _fp(gpu["master"]),

@@ -183,6 +183,7 @@ class Run:
                     g[pi] = bits
             h = self.host[c]
             h["grad"] = g
+            h["grad_f32"] = None if of else oracle.decode(g, w.dtype)     # decoded once for both comparisons
             old = dict(master=h["master"].copy(), exp_avg=h["exp_avg"].copy(), exp_avg_sq=h["exp_avg_sq"].copy())
             if self.split:
                 oracle.adamw_chunk(g, None, h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
@@ -210,7 +211,7 @@ class Run:
                 else:
                     free = self.free_bound[c].step(got, h, old, ctx, where + " (free-running)")
                     free.update(it=it, chunk=c)
-            del h["grad"]
+            del h["grad"], h["grad_f32"]
             return stats, free
 
         with cf.ThreadPoolExecutor(min(N_THREADS, len(self.sample))) as ex:
