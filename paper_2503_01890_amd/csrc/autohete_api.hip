@@ -475,12 +475,14 @@ int autohete_ws_tune(autohete_ws *ws, int knob, int64_t value)
         case AH_TUNE_CARRY_ELEMS: {
             /* Room for the per-wavefront partials that autohete_adamw_step_carry calls carry INTO this
              * workspace during one iteration over `value` elements: one slot per 64 * vec elements
-             * (current step variant) plus, per chunk descriptor, the waves of one ragged last tile. */
+             * (current step variant) plus, per chunk descriptor, the waves (at most 8) of one ragged last
+             * tile -- with room for eight times max_chunks descriptors per iteration, since a chunk may
+             * be cut into several descriptors by the per-block calls. */
             ah::StepVariant v;
             if (!decode_variant(ws->tune_step_variant, &v)) return AH_EINVAL;
             DeviceGuard g(ws->device);
             if (!g.ok) return AH_EHIP;
-            const uint64_t slots = (uint64_t)value / (uint64_t)(64 * v.vec) + (ws->max_chunks + 1) * 8;
+            const uint64_t slots = (uint64_t)value / (uint64_t)(64 * v.vec) + (ws->max_chunks + 1) * 64;
             if (slots <= ws->wave_partials_cap) return AH_OK;
             if (ws->carried_slots) return AH_EINVAL; /* a carried sum is pending: fold it first (read the result) */
             if (hipDeviceSynchronize() != hipSuccess) return AH_EHIP;
