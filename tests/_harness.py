@@ -131,9 +131,9 @@ def _parity_lib():
         L = ctypes.CDLL(build_parity_check())
         f32p, u16p, dp = ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_double)
         L.parity_strict.restype = None
-        L.parity_strict.argtypes = [ctypes.c_uint64] + [f32p] * 9 + [ctypes.POINTER(ParityConsts), dp]
+        L.parity_strict.argtypes = [ctypes.c_uint64, u16p, ctypes.c_int] + [f32p] * 8 + [ctypes.POINTER(ParityConsts), dp]
         L.parity_free.restype = None
-        L.parity_free.argtypes = [ctypes.c_uint64] + [f32p] * 12 + [ctypes.POINTER(ParityConsts), dp]
+        L.parity_free.argtypes = [ctypes.c_uint64, u16p, ctypes.c_int] + [f32p] * 11 + [ctypes.POINTER(ParityConsts), dp]
         L.parity_lowp.restype = ctypes.c_uint32
         L.parity_lowp.argtypes = [ctypes.c_uint64, u16p, u16p, ctypes.POINTER(ctypes.c_uint64)]
         _pc = L
@@ -193,11 +193,28 @@ def _lowp(gpu, ora, where, stats):
     return stats
 
 
-def _grad_f32(ora, ctx):
-    """The chunk's 16-bit gradients decoded by the oracle; callers that compare several device copies
-    against one oracle state may leave the decoded array under "grad_f32" to have it decoded once."""
-    gf = ora.get("grad_f32")
-    return gf if gf is not None else oracle.decode(ora["grad"], ctx.dtype)
+def _u16p(a):
+    if a is None:
+        return None
+    assert a.dtype == np.uint16 and a.flags.c_contiguous
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
+
+
+_scratch = threading.local()
+
+
+def keep_old(state):
+    """Copies of the three fp32 streams of `state` in this thread's reusable buffers (valid until
+    the thread's next call): the pre-step state the comparison rules need."""
+    bufs = getattr(_scratch, "old", None)
+    n = state["master"].size
+    if bufs is None or bufs["master"].size < n:
+        bufs = _scratch.old = {k: np.empty(n, np.float32) for k in _F32_STREAMS}
+    out = {}
+    for k in _F32_STREAMS:
+        out[k] = bufs[k][:n]
+        np.copyto(out[k], state[k])
+    return out
 
 
 def compare_state(gpu, ora, where="", old=None, ctx=None):
@@ -210,8 +227,8 @@ def compare_state(gpu, ora, where="", old=None, ctx=None):
     third = old is not None and ctx is not None and "grad" in ora
     raw = (ctypes.c_double * (3 * len(PS_FIELDS)))()
     k = ctx.consts() if third else ParityConsts()
-    gf = _grad_f32(ora, ctx) if third else None
-    _parity_lib().parity_strict(ora["master"].size, _fp(gf), _fp(old["exp_avg"]) if third else None,
+    _parity_lib().parity_strict(ora["master"].size, _u16p(ora["grad"]) if third else None, ctx.dtype if third else 0,
+                                _fp(old["exp_avg"]) if third else None,
                                 _fp(old["master"]) if third else None, _fp(ora["exp_avg"]), _fp(ora["exp_avg_sq"]),
                                 _fp(ora["master"]), _fp(gpu["exp_avg"]), _fp(gpu["exp_avg_sq"]), _fp(gpu["master"]),
                                 ctypes.byref(k), raw)
@@ -243,8 +260,7 @@ class FreeRun:
         assert ctx.rho is not None, "the bound needs the GPU's sum of squares"
         k = ctx.consts(ctx.rho)
         raw = (ctypes.c_double * (3 * len(PS_FIELDS)))()
-        gf = _grad_f32(ora, ctx)
-        _parity_lib().parity_free(ora["master"].size, _fp(gf), _fp(old["exp_avg"]), _fp(old["master"]),
+        _parity_lib().parity_free(ora["master"].size, _u16p(ora["grad"]), ctx.dtype, _fp(old["exp_avg"]), _fp(old["master"]),
                                   _fp(ora["exp_avg"]), _fp(ora["exp_avg_sq"]), _fp(ora["master"]),
                                   _fp(gpu["exp_avg"]), _fp(gpu["exp_avg_sq"]), _fp(gpu["master"]),
                                   _fp(self.D["exp_avg"]), _fp(self.D["exp_avg_sq"]), _fp(self.D["master"]),
@@ -282,15 +298,19 @@ def cpu_chunk_grad(w, c, iteration, loss_scale=None):
     return synthdata.fill_cpu(np.empty(w.chunk_elems, np.uint16), w.spec_grad(c, iteration, loss_scale))
 
 
-def oracle_sumsq_over_chunks(w, chunks, iteration, loss_scale, patch=None):
+def oracle_sumsq_over_chunks(w, chunks, iteration, loss_scale, patch=None, keep=None):
     """Oracle sum of squares / flag over the given chunk indices, regenerating each chunk's
     gradients on the CPU (threads; the C calls release the GIL).  Per-chunk sums are added in
-    chunk order.  patch: {(chunk, index): 16-bit pattern} overwrites applied before summing."""
+    chunk order.  patch: {(chunk, index): 16-bit pattern} overwrites applied before summing.
+    keep: a dict; the (patched) gradients of the chunks that are already keys of it are stored there
+    instead of being thrown away, for the caller's element-by-element replay."""
     def one(c):
         g = cpu_chunk_grad(w, c, iteration, loss_scale)
         for (pc, pi), bits in (patch or {}).items():
             if pc == c:
                 g[pi] = bits
+        if keep is not None and c in keep:
+            keep[c] = g
         return oracle.grad_accumulate(g, w.dtype, loss_scale if loss_scale else w.loss_scale)
     with cf.ThreadPoolExecutor(N_THREADS) as ex:
         parts = list(ex.map(one, chunks))

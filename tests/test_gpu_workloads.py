@@ -27,7 +27,7 @@ import torch
 
 import oracle
 import synthdata
-from _harness import (N_THREADS, FreeRun, StepCtx, compare_state, cpu_chunk_grad, cpu_chunk_state, download,
+from _harness import (N_THREADS, FreeRun, StepCtx, compare_state, cpu_chunk_grad, cpu_chunk_state, download, keep_old,
                       download_pinned, fill_device_chunk, oracle_hp, oracle_sumsq_over_chunks, resync, stream_handle,
                       bit_view)
 from paper_2503_01890_amd import binding as B
@@ -159,7 +159,8 @@ class Run:
         if self.shadows:       # the free-running copy: same kernel, same norm (still in the workspace)
             self.ws.autohete_adamw_step(self.free_arr, len(self.sample), w.dtype, self.t, hp, st)
         # oracle: norm over every resident chunk (runs while the GPU works), then the sampled chunks
-        s, f = oracle_sumsq_over_chunks(w, range(w.n_resident), it, scale, patch)
+        grads = dict.fromkeys(self.sample)          # the sampled chunks' gradients are kept for their replay
+        s, f = oracle_sumsq_over_chunks(w, range(w.n_resident), it, scale, patch, keep=grads)
         on, of = oracle.grad_finish(s + extra, f)
         if self.shadows:       # the exact-mode copy is handed the ORACLE's sum of squares and flag
             self.ws_exact.autohete_grad_result_set(s + extra, of, st)
@@ -177,14 +178,10 @@ class Run:
 
         def oracle_step(j):          # oracle update of one chunk, then its comparison with the device's three
             c = self.sample[j]       # copies; runs in a worker thread (the C calls and numpy release the GIL)
-            g = cpu_chunk_grad(w, c, it, scale)
-            for (pc, pi), bits in patch.items():
-                if pc == c:
-                    g[pi] = bits
+            g = grads.pop(c)         # regenerated (and patched) by the norm pass above
             h = self.host[c]
             h["grad"] = g
-            h["grad_f32"] = None if of else oracle.decode(g, w.dtype)     # decoded once for both comparisons
-            old = dict(master=h["master"].copy(), exp_avg=h["exp_avg"].copy(), exp_avg_sq=h["exp_avg_sq"].copy())
+            old = keep_old(h)
             if self.split:
                 oracle.adamw_chunk(g, None, h["master"], h["exp_avg"], h["exp_avg_sq"], w.dtype, self.t,
                                    oracle_hp(hp), on, of)
@@ -211,7 +208,7 @@ class Run:
                 else:
                     free = self.free_bound[c].step(got, h, old, ctx, where + " (free-running)")
                     free.update(it=it, chunk=c)
-            del h["grad"], h["grad_f32"]
+            del h["grad"]
             return stats, free
 
         with cf.ThreadPoolExecutor(min(N_THREADS, len(self.sample))) as ex:

@@ -176,3 +176,33 @@ def test_host_step_degenerate_states(simd):
         assert np.array_equal(nan16(st["param_lp"]), nan16(ref["param_lp"]))
         ok = ~nan16(ref["param_lp"])
         assert np.array_equal(st["param_lp"][ok], ref["param_lp"][ok])
+
+
+def test_bias_correction_quotients_without_division_are_the_quotients():
+    """The AVX-512 path forms x / (1 - beta^t) from the correctly rounded reciprocal and two fused
+    multiply-adds instead of a division.  That is the correctly rounded quotient by theorem; here it
+    is held to the oracle's divisions bit for bit over 150 step numbers (each its own pair of
+    divisors, including beta = 0 -> divisor 1), states that span forty binades, and gradients that
+    include both zeros -- 20 million quotients."""
+    B.raw().autohete_host_force_scalar(0)
+    rng = np.random.default_rng(2024)
+    n = 1 << 16
+    steps = [1, 2, 3, 4, 5, 7, 10, 100, 1000, 10_000, 123_457] + [int(x) for x in rng.integers(1, 5000, 139)]
+    for k, step in enumerate(steps):
+        beta1, beta2 = (0.0, 0.0) if k == 0 else (float(rng.choice([0.9, 0.5, 0.99])), float(rng.choice([0.999, 0.95, 0.9])))
+        hp = B.hparams(beta1=beta1, beta2=beta2, max_grad_norm=0.0, lr=1e-3, eps=1e-8)
+        ohp = oracle.hparams(beta1=beta1, beta2=beta2, max_grad_norm=0.0, lr=1e-3, eps=1e-8)
+        mag = lambda: np.exp2(rng.uniform(-30, 10, n))
+        grad = lowp(rng.normal(0, 1, n) * mag(), B.AH_BF16)
+        grad[:64] = np.where(np.arange(64) % 2, 0x8000, 0x0000)          # -0 and +0 gradients
+        st = dict(grad=grad, param_lp=np.zeros(n, np.uint16), master=(rng.normal(0, 1, n) * mag()).astype(np.float32),
+                  exp_avg=(rng.normal(0, 1, n) * mag()).astype(np.float32),
+                  exp_avg_sq=(mag() ** 2).astype(np.float32))
+        st["exp_avg"][:32] = np.where(np.arange(32) % 4 < 2, -0.0, 0.0)   # zero moments of both signs
+        st["exp_avg_sq"][:16] = 0.0
+        ref = {k_: v.copy() for k_, v in st.items()}
+        B.autohete_host_adamw_step(host_chunks([st]), 1, B.AH_BF16, step, hp, 1.0, 0, 4)
+        oracle.adamw_chunk(ref["grad"], ref["param_lp"], ref["master"], ref["exp_avg"], ref["exp_avg_sq"], B.AH_BF16,
+                           step, ohp, 1.0, 0)
+        for key in st:
+            assert st[key].tobytes() == ref[key].tobytes(), (step, beta1, beta2, key)
