@@ -27,6 +27,8 @@ namespace {
 
 struct Consts {
     double inv, coef, b1, b2, omb1, omb2, bc1, bc2, lr, eps, wd;
+    double rbc1, rbc2;   /* correctly rounded reciprocals of bc1, bc2 */
+    bool recip_exact;    /* the quotients by bc1 / bc2 may be formed from them (see div_by_const) */
 };
 
 /* ---------------------------------------------------------------- scalar 16-bit conversions */
@@ -102,7 +104,24 @@ inline double sumsq_scalar(const uint16_t *g, size_t lo, size_t hi, int dtype)
 
 /* ---------------------------------------------------------------- AVX-512 (8 elements per step) */
 
-#define AH_AVX512 __attribute__((target("avx512f,avx512dq,avx512bw,avx512vl,f16c")))
+#define AH_AVX512 __attribute__((target("avx512f,avx512dq,avx512bw,avx512vl,f16c,fma")))
+
+/* a / b, correctly rounded, for a divisor b that is the same for every element, without a division
+ * instruction: with y = RN(1 / b) computed once, q = RN(a y) is within one ulp of the quotient, the
+ * residual r = a - b q is exact in a fused multiply-add, and RN(q + r y) is the correctly rounded
+ * quotient (Markstein's theorem on division by fused multiply-add; it needs y within half an ulp of
+ * 1 / b, which fails only for a divisor whose significand is all ones -- checked once per call by
+ * recip_is_safe -- and no zero, infinity, NaN or subnormal a, for which the vector falls back to the
+ * division instruction).  The two bias-correction quotients are two thirds of the divisions of the
+ * update; a 512-bit division costs as much as a dozen multiplications. */
+AH_AVX512 inline __m512d div_by_const(__m512d a, __m512d b, __m512d y)
+{
+    /* classes: QNaN 0x01, +0 0x02, -0 0x04, +inf 0x08, -inf 0x10, denormal 0x20, SNaN 0x80 */
+    if (__builtin_expect(_mm512_fpclass_pd_mask(a, 0xBF) != 0, 0)) return _mm512_div_pd(a, b);
+    const __m512d q = _mm512_mul_pd(a, y);
+    const __m512d r = _mm512_fnmadd_pd(b, q, a);
+    return _mm512_fmadd_pd(r, y, q);
+}
 
 AH_AVX512 inline __m512d load8_lowp(const uint16_t *g, int dtype)
 {
@@ -134,7 +153,9 @@ AH_AVX512 void step_avx512(const uint16_t *g, uint16_t *q, float *p, float *m, f
     const __m512d inv = _mm512_set1_pd(k.inv), coef = _mm512_set1_pd(k.coef), b1 = _mm512_set1_pd(k.b1),
                   b2 = _mm512_set1_pd(k.b2), omb1 = _mm512_set1_pd(k.omb1), omb2 = _mm512_set1_pd(k.omb2),
                   bc1 = _mm512_set1_pd(k.bc1), bc2 = _mm512_set1_pd(k.bc2), lr = _mm512_set1_pd(k.lr),
-                  eps = _mm512_set1_pd(k.eps), wd = _mm512_set1_pd(k.wd);
+                  eps = _mm512_set1_pd(k.eps), wd = _mm512_set1_pd(k.wd), rbc1 = _mm512_set1_pd(k.rbc1),
+                  rbc2 = _mm512_set1_pd(k.rbc2);
+    const bool recip = k.recip_exact;
     size_t i = lo;
     for (; i + 8 <= hi; i += 8) {
         const __m512d gd = _mm512_mul_pd(_mm512_mul_pd(load8_lowp(g + i, dtype), inv), coef);
@@ -143,8 +164,10 @@ AH_AVX512 void step_avx512(const uint16_t *g, uint16_t *q, float *p, float *m, f
         const __m512d vd = _mm512_cvtps_pd(_mm256_loadu_ps(v + i));
         const __m512d mn = _mm512_add_pd(_mm512_mul_pd(b1, md), _mm512_mul_pd(omb1, gd));
         const __m512d vn = _mm512_add_pd(_mm512_mul_pd(b2, vd), _mm512_mul_pd(omb2, _mm512_mul_pd(gd, gd)));
-        const __m512d den = _mm512_add_pd(_mm512_sqrt_pd(_mm512_div_pd(vn, bc2)), eps);
-        const __m512d upd = _mm512_div_pd(_mm512_div_pd(mn, bc1), den);
+        const __m512d vh = recip ? div_by_const(vn, bc2, rbc2) : _mm512_div_pd(vn, bc2);
+        const __m512d mh = recip ? div_by_const(mn, bc1, rbc1) : _mm512_div_pd(mn, bc1);
+        const __m512d den = _mm512_add_pd(_mm512_sqrt_pd(vh), eps);
+        const __m512d upd = _mm512_div_pd(mh, den);
         const __m512d pn = _mm512_sub_pd(pd, _mm512_mul_pd(lr, _mm512_add_pd(upd, _mm512_mul_pd(wd, pd))));
         const __m256 pf = _mm512_cvtpd_ps(pn);
         _mm256_storeu_ps(m + i, _mm512_cvtpd_ps(mn));
@@ -178,7 +201,7 @@ bool have_avx512()
     if (g_force_scalar) return false;
     static const bool ok = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512dq") &&
                            __builtin_cpu_supports("avx512bw") && __builtin_cpu_supports("avx512vl") &&
-                           __builtin_cpu_supports("f16c");
+                           __builtin_cpu_supports("f16c") && __builtin_cpu_supports("fma");
     return ok;
 }
 
@@ -215,6 +238,16 @@ void for_slices(const autohete_chunk *chunks, uint64_t n, int n_threads, F fn)
     }
     work(0);
     for (std::thread &th : pool) th.join();
+}
+
+/* Is RN(1 / b) within half an ulp of 1 / b in the sense div_by_const needs?  Always, except for a
+ * divisor whose significand is all ones; b must also be a normal number. */
+bool recip_is_safe(double b)
+{
+    uint64_t u;
+    memcpy(&u, &b, 8);
+    const uint64_t frac = u & 0x000FFFFFFFFFFFFFull, e = (u >> 52) & 0x7FFull;
+    return b > 0.0 && e != 0 && e != 0x7FF && frac != 0x000FFFFFFFFFFFFFull;
 }
 
 int check_host_args(const autohete_chunk *chunks, uint64_t n, int dtype, int n_threads, unsigned need)
@@ -294,6 +327,9 @@ int autohete_host_adamw_step(const autohete_chunk *chunks, uint64_t n_chunks, in
     k.lr = (double)hp->lr;
     k.eps = (double)hp->eps;
     k.wd = (double)hp->weight_decay;
+    k.rbc1 = 1.0 / k.bc1;
+    k.rbc2 = 1.0 / k.bc2;
+    k.recip_exact = recip_is_safe(k.bc1) && recip_is_safe(k.bc2);
     try {
         const bool vec = have_avx512();
         for_slices(chunks, n_chunks, n_threads, [&](uint64_t c, size_t lo, size_t hi, int) {
