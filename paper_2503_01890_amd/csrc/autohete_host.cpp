@@ -147,6 +147,12 @@ AH_AVX512 inline void store8_lowp(uint16_t *q, __m256 f, int dtype)
     _mm_storeu_si128(reinterpret_cast<__m128i *>(q), h);
 }
 
+/* Software prefetch distance in elements (8 KB of each fp32 stream).  One core's demand misses alone
+ * do not keep enough lines in flight for five streams: on the 16 threads of the GPU machine's host the
+ * update runs at 10.4 G parameters/s without prefetches, 10.9 / 11.4 / 11.7 / 11.8 / 11.3 / 11.0 with
+ * 256 / 512 / 1024 / 2048 / 4096 / 8192 elements ahead.  A prefetch beyond the end of an array is harmless. */
+constexpr size_t kPrefetch = 2048;
+
 AH_AVX512 void step_avx512(const uint16_t *g, uint16_t *q, float *p, float *m, float *v, size_t lo, size_t hi,
                            int dtype, const Consts &k)
 {
@@ -158,6 +164,12 @@ AH_AVX512 void step_avx512(const uint16_t *g, uint16_t *q, float *p, float *m, f
     const bool recip = k.recip_exact;
     size_t i = lo;
     for (; i + 8 <= hi; i += 8) {
+        if ((i & 8) == 0) { /* once per 64-byte line of the fp32 streams: ask for the lines kPrefetch elements ahead */
+            _mm_prefetch(reinterpret_cast<const char *>(p + i + kPrefetch), _MM_HINT_T0);
+            _mm_prefetch(reinterpret_cast<const char *>(m + i + kPrefetch), _MM_HINT_T0);
+            _mm_prefetch(reinterpret_cast<const char *>(v + i + kPrefetch), _MM_HINT_T0);
+            if ((i & 16) == 0) _mm_prefetch(reinterpret_cast<const char *>(g + i + kPrefetch), _MM_HINT_T0);
+        }
         const __m512d gd = _mm512_mul_pd(_mm512_mul_pd(load8_lowp(g + i, dtype), inv), coef);
         const __m512d pd = _mm512_cvtps_pd(_mm256_loadu_ps(p + i));
         const __m512d md = _mm512_cvtps_pd(_mm256_loadu_ps(m + i));
