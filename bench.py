@@ -61,6 +61,8 @@ def parse():
     ap.add_argument("--step-variant", type=lambda x: int(x, 0), default=0, help="AH_TUNE_STEP_VARIANT value (0 = default)")
     ap.add_argument("--blocks-per-cu", type=int, default=0, help="AH_TUNE_STEP_BLOCKS_PER_CU (0 = default)")
     ap.add_argument("--prep-blocks", type=int, default=0, help="AH_TUNE_PREP_BLOCKS (0 = default)")
+    ap.add_argument("--blocks-per-call", type=int, default=1,
+                    help="per_block_carry path: optimizer partitions (transformer blocks) stepped by one call")
     ap.add_argument("--graph", action="store_true",
                     help="fused path only: record each step (prep + update) into a HIP graph once and time replays")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -245,6 +247,8 @@ def measure(res, path, steps, warmup, args):
             x.tune(B.AH_TUNE_CARRY_ELEMS, elems)
         other.tune(B.AH_TUNE_STEP_BLOCKS_PER_CU, args.blocks_per_cu)
         bounds = w.partition_bounds()
+        per_call = max(1, getattr(args, "blocks_per_call", 1))
+        bounds = bounds[:-1][::per_call] + bounds[-1:]         # several adjacent partitions per call
         parts = []
         for s in range(res.n_sets):
             per_set = []
