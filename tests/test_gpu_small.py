@@ -135,7 +135,9 @@ def test_hand_worked_examples_through_hip():
         dtype = B.AH_BF16 if c["dtype"] == "bf16" else B.AH_FP16
         hp = B.hparams(c["lr"], c["beta1"], c["beta2"], c["eps"], c["weight_decay"], c["max_grad_norm"],
                        c["loss_scale"])
-        g = torch.tensor(c["grad"], dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        g = torch.tensor(c["grad"], dtype=torch.float32).to(torch.bfloat16 if dtype == B.AH_BF16 else torch.float16)
+        g = g.view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(oracle.decode(g, dtype).astype(np.float64), c["grad"]), "fixture gradients must be exact in 16 bits"
         st = dict(grad=g.copy(), param_lp=np.zeros(16, np.uint16), master=c["master"].astype(np.float32),
                   exp_avg=c["exp_avg"].astype(np.float32), exp_avg_sq=c["exp_avg_sq"].astype(np.float32))
         md = ModelData([16])
