@@ -206,3 +206,22 @@ def test_bias_correction_quotients_without_division_are_the_quotients():
                            step, ohp, 1.0, 0)
         for key in st:
             assert st[key].tobytes() == ref[key].tobytes(), (step, beta1, beta2, key)
+
+
+def test_hand_worked_examples_through_the_host_optimizer(simd):
+    """The 16-element examples worked by hand (tests/golden/adamw_hand_worked.txt), through the
+    library's host path: every expected value is met exactly."""
+    from _golden import load_hand_worked
+    for name, c in load_hand_worked().items():
+        dtype = B.AH_BF16 if c["dtype"] == "bf16" else B.AH_FP16
+        hp = B.hparams(c["lr"], c["beta1"], c["beta2"], c["eps"], c["weight_decay"], c["max_grad_norm"], c["loss_scale"])
+        st = dict(grad=lowp(c["grad"], dtype), param_lp=np.zeros(16, np.uint16), master=c["master"].astype(np.float32),
+                  exp_avg=c["exp_avg"].astype(np.float32), exp_avg_sq=c["exp_avg_sq"].astype(np.float32))
+        arr = host_chunks([st])
+        for k in range(1, int(c["steps"]) + 1):
+            sumsq, flag = B.autohete_host_grad_sumsq(arr, 1, dtype, c["loss_scale"], 2)
+            assert flag == 0 and sumsq == pytest.approx(c["expect_sumsq"], rel=1e-15), name
+            B.autohete_host_adamw_step(arr, 1, dtype, int(c["first_step"]) + k - 1, hp, sumsq, flag, 2)
+            for key in ("master", "exp_avg", "exp_avg_sq"):
+                assert np.array_equal(st[key], c["expect_%s_t%d" % (key, k)].astype(np.float32)), (name, key, k)
+            assert np.array_equal(oracle.decode(st["param_lp"], dtype).astype(np.float64), c["expect_param_lp_t%d" % k]), name
