@@ -61,6 +61,7 @@ def parse():
     ap.add_argument("--step-variant", type=lambda x: int(x, 0), default=0, help="AH_TUNE_STEP_VARIANT value (0 = default)")
     ap.add_argument("--blocks-per-cu", type=int, default=0, help="AH_TUNE_STEP_BLOCKS_PER_CU (0 = default)")
     ap.add_argument("--prep-blocks", type=int, default=0, help="AH_TUNE_PREP_BLOCKS (0 = default)")
+    ap.add_argument("--cast-blocks-per-cu", type=int, default=0, help="AH_TUNE_CAST_BLOCKS_PER_CU (0 = default)")
     ap.add_argument("--blocks-per-call", type=int, default=1,
                     help="per_block_carry path: optimizer partitions (transformer blocks) stepped by one call")
     ap.add_argument("--graph", action="store_true",
@@ -234,6 +235,7 @@ def measure(res, path, steps, warmup, args):
     ws.tune(B.AH_TUNE_STEP_VARIANT, args.step_variant)
     ws.tune(B.AH_TUNE_STEP_BLOCKS_PER_CU, args.blocks_per_cu)
     ws.tune(B.AH_TUNE_PREP_BLOCKS, args.prep_blocks)
+    ws.tune(B.AH_TUNE_CAST_BLOCKS_PER_CU, getattr(args, "cast_blocks_per_cu", 0))
     hp = B.hparams(**w.hparams, loss_scale=w.loss_scale)
     n_ev = {"fused": 3, "split": 4, "per_block_carry": 2}[path]
 
