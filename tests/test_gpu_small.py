@@ -1242,3 +1242,29 @@ def test_prep_and_step_captured_in_a_hip_graph_replay_like_eager_calls():
             assert all(a[k].tobytes() == b[k].tobytes() for k in STREAMS), (rep, i)
     assert float(scratch[0]) == 4.0
     ws_g.close(), ws_e.close()
+
+
+def test_bench_prints_one_json_line_with_the_contract_keys():
+    """bench.py on the smallest configuration (a process of its own): exactly one JSON line with the
+    metric, the timing fields, a roofline object for the dominant kernel and the workload name."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "gpt-124m", "--steps", "5",
+                          "--warmup", "2", "--no-cpu-baseline"], capture_output=True, text=True, timeout=280)
+    assert run.returncode == 0, run.stderr[-2000:]
+    lines = [ln for ln in run.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "hbm"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2 and d["unit"] == "params/s" and d["data"] == "synthetic"
+    assert d["config"]["workload"] == "gpt-124m" and d["vs_baseline"] is None and d["higher_is_better"] is True
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s" and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12
+    assert r["traffic_source"] == "profiles/adamw_step_kernel_gpt-124m_pmc.txt" and r["traffic"] > 0
+    assert 0.3 < r["frac"] < 1.0 and 0 < d["ms_per_step"] < 5.0
+    assert abs(d["value"] - d["config"]["resident_params"] / (d["ms_per_step"] * 1e-3)) <= 1e-6 * d["value"]
