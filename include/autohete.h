@@ -245,7 +245,8 @@ int autohete_grad_result_set(autohete_ws *ws, double sumsq, uint32_t found_inf, 
 enum {
     AH_TUNE_STEP_BLOCKS_PER_CU = 0, /* cap on step-kernel blocks resident per CU: 3..64 (64 = no
                                        cap; 1 and 2 cannot be enforced and are refused with
-                                       AH_EINVAL); 0 = default                                 */
+                                       AH_EINVAL); 0 = default: chosen per call from the
+                                       elements it covers (10 to 12; shorter calls take more)  */
     AH_TUNE_PREP_BLOCKS = 1,        /* thread blocks of the prep kernel; 0 = default           */
     AH_TUNE_CAST_BLOCKS_PER_CU = 3, /* the same cap for the cast kernel; 0 = default           */
     AH_TUNE_CARRY_ELEMS = 4,        /* elements that autohete_adamw_step_carry calls carry INTO
